@@ -1,0 +1,18 @@
+"""Fused learnable-scale fake quantization for MI355X (gfx950).
+
+`workloads` generates seeded synthetic inputs (numpy only).  The GPU entry points live in
+`binding` (thin ctypes marshalling onto the C-ABI library built from csrc/); it is imported
+on first use and raises if the compiled library is missing -- there is no CPU fallback.
+"""
+from . import workloads  # noqa: F401
+
+_API = ("fq_forward", "fq_backward", "fq_multi_tensor", "fq_workspace_bytes", "fq_validate",
+        "fq_status_string", "FqTensor", "FqError", "library_path")
+
+
+def __getattr__(name):
+    if name == "binding" or name in _API:
+        import importlib
+        mod = importlib.import_module(__name__ + ".binding")
+        return mod if name == "binding" else getattr(mod, name)
+    raise AttributeError(name)
