@@ -1,0 +1,138 @@
+/*
+ * libfq -- fused learnable-scale fake quantization for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every tensor pointer in fq_tensor is a DEVICE pointer owned by the
+ * caller; descriptor structs and arrays of them are HOST memory.  The library
+ * enqueues kernels on the given HIP stream and returns; it never synchronises
+ * the device and never allocates or frees device memory.  All functions return
+ * an fq_status (0 = success, negative = failure); validation happens before
+ * anything is enqueued, so a failing call has no device side effects.  Nothing
+ * throws or aborts across this boundary.
+ *
+ * The operation (DPVO-QAT++, Sec. 3.2):
+ *   scale     s_c = clip(softplus(theta_c) + eps, s_min, s_max)        Eq. (3)-(4)
+ *   forward   y   = s_c * round(clip(x / s_c, qmin, qmax))             Eq. (5)-(6)
+ *   backward  straight-through estimator (round differentiated as identity):
+ *             gx = gy where qmin <= x/s_c <= qmax, else +0
+ *             gs_c = sum over the channel of gy * t,
+ *                    t = round(x/s_c) - x/s_c inside the range, qmin below, qmax above
+ *             gtheta_c = gs_c * sigmoid(theta_c), or 0 where the clip of Eq. (3)-(4) is active
+ * round() is round-half-to-even; x/s is the correctly rounded binary32 quotient;
+ * all arithmetic is binary32 (softplus/sigmoid evaluated in binary64 and rounded
+ * once); FP16 tensors are widened exactly and narrowed with round-to-nearest-even
+ * (Sec. 3.3 "Mixed precision").  Results are bitwise reproducible run to run.
+ *
+ * Layout: every tensor is a contiguous [outer, channels, inner] array; element
+ * (o, c, k) uses scale c.
+ *   per-channel NCHW activation:        outer = N, channels = C,     inner = H*W
+ *   per-output-channel conv weight:     outer = 1, channels = C_out, inner = C_in*kh*kw
+ *   per-tensor (the paper's activations): outer = 1, channels = 1,   inner = numel
+ */
+#ifndef FQ_H
+#define FQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fq_status {
+    FQ_OK = 0,
+    FQ_ERR_NULL = -1,          /* a required pointer is NULL */
+    FQ_ERR_DTYPE = -2,         /* dtype is not FQ_F16 / FQ_F32 */
+    FQ_ERR_SHAPE = -3,         /* negative extent, element/slab/block count overflow, bad n or mode */
+    FQ_ERR_QRANGE = -4,        /* need qmin <= 0 <= qmax, qmin < qmax, |q| <= 32768; int8 codes need [-128,127] */
+    FQ_ERR_ALIGN = -5,         /* pointer not aligned to its element size (workspace: 256 bytes) */
+    FQ_ERR_WORKSPACE = -6,     /* workspace NULL or smaller than fq_workspace_bytes() */
+    FQ_ERR_SCALE_PARAMS = -7,  /* need finite eps, 0 < s_min <= s_max, no NaN */
+    FQ_ERR_LAUNCH = -8,        /* the HIP runtime reported an error while enqueuing */
+    FQ_ERR_ALIAS = -9          /* output partially overlaps its input (exact in-place is allowed) */
+} fq_status;
+
+typedef enum fq_dtype { FQ_F16 = 0, FQ_F32 = 1 } fq_dtype;
+
+enum {
+    /* Backward: do not write gx.  For tensors whose values are frozen and only the
+       scales train (the paper's weights, Sec. 3.2 "Scale-Only QAT"). */
+    FQ_FLAG_NO_DX = 1u,
+    /* Backward: finish the per-channel scale gradient in a second small kernel instead
+       of in the last block of each channel.  Same results bit for bit. */
+    FQ_FLAG_TWO_PASS = 2u
+};
+
+enum { FQ_MODE_FORWARD = 1, FQ_MODE_BACKWARD = 2 };
+
+/* One tensor to fake-quantize.  Host struct; the pointers inside are device pointers. */
+typedef struct fq_tensor {
+    int64_t outer, channels, inner;   /* contiguous [outer, channels, inner]; any extent may be 0 */
+    int32_t dtype;                    /* fq_dtype of x, y, gy, gx */
+    int32_t qmin, qmax;               /* integer code range; paper: -127..127 (Eq. (5)-(6)) */
+    float eps, s_min, s_max;          /* Eq. (3)-(4); plain softplus: eps = 0, s_min = FLT_MIN, s_max = +inf */
+    uint32_t flags;                   /* FQ_FLAG_* */
+    const void *x;                    /* in  (forward and backward) */
+    void *y;                          /* out (forward); may be exactly x (in place) */
+    int8_t *q;                        /* out (forward), optional: integer codes, 0 where x is NaN */
+    const float *theta;               /* in  [channels], the learnable parameter ("log scale") */
+    float *s;                         /* out [channels], optional: the scales used (forward and backward) */
+    const void *gy;                   /* in  (backward): upstream gradient, same dtype/shape as x */
+    void *gx;                         /* out (backward); may be exactly gy; unused with FQ_FLAG_NO_DX */
+    float *gs;                        /* out [channels], optional: dL/ds (overwritten) */
+    float *gtheta;                    /* out [channels], optional: dL/dtheta (overwritten) */
+} fq_tensor;
+
+/*
+ * Bytes of device workspace that fq_backward / fq_multi_tensor need for these n tensors
+ * in this mode (a multiple of 256; at least 256).  Pure host function, touches no GPU.
+ * Returns 0 if the descriptors do not validate.
+ */
+size_t fq_workspace_bytes(const fq_tensor *ts, int n, int mode);
+
+/*
+ * Check n descriptors for the given mode exactly as the launching calls do (everything
+ * except the workspace).  Pure host function, touches no GPU.
+ */
+fq_status fq_validate(const fq_tensor *ts, int n, int mode);
+
+/*
+ * Zero a workspace on `stream` (a fill kernel, not a memset, so it may be captured in a
+ * HIP graph).  A workspace must be zeroed once before its first use by fq_backward /
+ * fq_multi_tensor in backward mode (memory that is already all zero, e.g. torch.zeros,
+ * qualifies); every completed call leaves it ready for the next one.  One workspace must
+ * not be used by two calls that can overlap in time.
+ */
+fq_status fq_workspace_init(void *workspace, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Forward, Eq. (3)-(5), one launch: reads x, theta; writes y and, if non-NULL, q and s.
+ * A tensor with zero elements is a no-op (s is still written).
+ */
+fq_status fq_forward(const fq_tensor *t, void *hip_stream);
+
+/*
+ * STE backward for one tensor: reads x, gy, theta; writes gx (unless FQ_FLAG_NO_DX) and,
+ * if non-NULL, gs, gtheta, s.  x is re-read and the quotient recomputed, nothing is saved
+ * by the forward.  One launch (two with FQ_FLAG_TWO_PASS).  No float atomics: per-block
+ * partial sums go to the workspace and are added in a fixed order.
+ */
+fq_status fq_backward(const fq_tensor *t, void *workspace, size_t ws_bytes, void *hip_stream);
+
+/*
+ * The same forward (mode FQ_MODE_FORWARD) or backward (FQ_MODE_BACKWARD) for a whole list
+ * of tensors -- e.g. the activations and weights of all 22 quantized convolutions of the
+ * front end (Sec. 4.3.4 "Quantization coverage") -- in ONE kernel launch instead of one to three per layer
+ * (Sec. 3.3).  `ts` is a host array of n descriptors; it is copied to the start of the
+ * workspace on `stream` and may be reused as soon as the call returns.  n = 0 is a no-op.
+ * FQ_FLAG_TWO_PASS on any tensor selects the two-launch backward for the whole list.
+ */
+fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode,
+                          void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *fq_status_string(fq_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FQ_H */

@@ -1,0 +1,168 @@
+"""Thin ctypes binding of the C ABI in include/fq.h (same names, argument marshalling only).
+
+Every step of the computation runs in the HIP kernels of libfq.so; nothing here does
+arithmetic on tensor data and there is no CPU fallback: importing this module raises if the
+compiled library is missing (build it with `python -m paper_2511_12653_amd.build` or
+`__graft_entry__.build()`).
+
+PyTorch is used by callers only to own device memory and streams; `FqTensor.from_torch`
+reads data pointers and shapes from torch tensors, and `stream=None` means torch's current
+stream.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfq.so")
+
+FQ_F16, FQ_F32 = 0, 1
+FQ_FLAG_NO_DX, FQ_FLAG_TWO_PASS = 1, 2
+FQ_MODE_FORWARD, FQ_MODE_BACKWARD = 1, 2
+FLT_MIN = 1.1754943508222875e-38
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            "libfq.so is not built (%s missing); run `python -m paper_2511_12653_amd.build`. "
+            "There is no CPU fallback." % _LIB_PATH)
+    return ctypes.CDLL(_LIB_PATH)
+
+
+class FqTensor(ctypes.Structure):
+    """Mirror of `struct fq_tensor` (host struct holding device pointers)."""
+    _fields_ = [
+        ("outer", ctypes.c_int64), ("channels", ctypes.c_int64), ("inner", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("qmin", ctypes.c_int32), ("qmax", ctypes.c_int32),
+        ("eps", ctypes.c_float), ("s_min", ctypes.c_float), ("s_max", ctypes.c_float),
+        ("flags", ctypes.c_uint32),
+        ("x", ctypes.c_void_p), ("y", ctypes.c_void_p), ("q", ctypes.c_void_p),
+        ("theta", ctypes.c_void_p), ("s", ctypes.c_void_p),
+        ("gy", ctypes.c_void_p), ("gx", ctypes.c_void_p),
+        ("gs", ctypes.c_void_p), ("gtheta", ctypes.c_void_p),
+    ]
+
+    @classmethod
+    def from_torch(cls, outer, channels, inner, qmin, qmax, x=None, y=None, q=None, theta=None,
+                   s=None, gy=None, gx=None, gs=None, gtheta=None, eps=0.0, s_min=FLT_MIN,
+                   s_max=float("inf"), flags=0, dtype=None):
+        """Marshal torch tensors (device memory owned by the caller) into a descriptor."""
+        import torch
+
+        def ptr(t, want_dtype=None):
+            if t is None:
+                return None
+            if not t.is_contiguous():
+                raise ValueError("tensors must be contiguous")
+            if want_dtype is not None and t.dtype != want_dtype:
+                raise TypeError("expected %s, got %s" % (want_dtype, t.dtype))
+            return t.data_ptr()
+
+        ref = x if x is not None else gy
+        if dtype is None:
+            if ref is None:
+                raise ValueError("dtype needed when no data tensor is given")
+            dtype = {torch.float16: FQ_F16, torch.float32: FQ_F32}[ref.dtype]
+        tdt = torch.float16 if dtype == FQ_F16 else torch.float32
+        n = outer * channels * inner
+        for t in (x, y, gy, gx, q):
+            if t is not None and t.numel() != n:
+                raise ValueError("tensor has %d elements, view says %d" % (t.numel(), n))
+        for t in (theta, s, gs, gtheta):
+            if t is not None and t.numel() != channels:
+                raise ValueError("per-channel tensor has %d elements, want %d" % (t.numel(), channels))
+        return cls(outer, channels, inner, dtype, qmin, qmax, eps, s_min, s_max, flags,
+                   ptr(x, tdt), ptr(y, tdt), ptr(q, torch.int8), ptr(theta, torch.float32),
+                   ptr(s, torch.float32), ptr(gy, tdt), ptr(gx, tdt), ptr(gs, torch.float32),
+                   ptr(gtheta, torch.float32))
+
+
+class FqError(RuntimeError):
+    def __init__(self, status):
+        self.status = int(status)
+        super().__init__("libfq: %s (status %d)" % (fq_status_string(status), status))
+
+
+_lib = _load()
+_lib.fq_workspace_bytes.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_int, ctypes.c_int]
+_lib.fq_workspace_bytes.restype = ctypes.c_size_t
+_lib.fq_validate.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_int, ctypes.c_int]
+_lib.fq_validate.restype = ctypes.c_int
+_lib.fq_workspace_init.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fq_workspace_init.restype = ctypes.c_int
+_lib.fq_forward.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_void_p]
+_lib.fq_forward.restype = ctypes.c_int
+_lib.fq_backward.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fq_backward.restype = ctypes.c_int
+_lib.fq_multi_tensor.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_int, ctypes.c_int,
+                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fq_multi_tensor.restype = ctypes.c_int
+_lib.fq_status_string.argtypes = [ctypes.c_int]
+_lib.fq_status_string.restype = ctypes.c_char_p
+
+
+def _array(tensors):
+    if isinstance(tensors, FqTensor):
+        tensors = [tensors]
+    tensors = list(tensors)
+    arr = (FqTensor * max(1, len(tensors)))(*tensors)
+    return arr, len(tensors)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    if isinstance(workspace, tuple):
+        return workspace
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def _check(status):
+    if status != 0:
+        raise FqError(status)
+
+
+def fq_status_string(status) -> str:
+    return _lib.fq_status_string(int(status)).decode()
+
+
+def fq_workspace_bytes(tensors, mode) -> int:
+    arr, n = _array(tensors)
+    return int(_lib.fq_workspace_bytes(arr, n, mode))
+
+
+def fq_validate(tensors, mode) -> int:
+    """Returns the fq_status (0 = ok) without raising."""
+    arr, n = _array(tensors)
+    return int(_lib.fq_validate(arr, n, mode))
+
+
+def fq_workspace_init(workspace, stream=None):
+    p, nbytes = _ws(workspace)
+    _check(_lib.fq_workspace_init(p, nbytes, _stream(stream)))
+
+
+def fq_forward(t: FqTensor, stream=None):
+    _check(_lib.fq_forward(ctypes.byref(t), _stream(stream)))
+
+
+def fq_backward(t: FqTensor, workspace, stream=None):
+    p, nbytes = _ws(workspace)
+    _check(_lib.fq_backward(ctypes.byref(t), p, nbytes, _stream(stream)))
+
+
+def fq_multi_tensor(tensors, mode, workspace, stream=None):
+    arr, n = _array(tensors)
+    p, nbytes = _ws(workspace)
+    _check(_lib.fq_multi_tensor(arr, n, mode, p, nbytes, _stream(stream)))

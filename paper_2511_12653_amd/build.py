@@ -1,0 +1,39 @@
+"""Compile the gfx950 kernels and the C-ABI host code into paper_2511_12653_amd/libfq.so.
+
+hipcc cross-compiles for gfx950 without a GPU.  Flags: IEEE arithmetic only (no fast-math, no
+implicit FMA contraction -- the kernels call fma explicitly where they want one) and no packed
+FP32 instructions.
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libfq.so")
+SOURCES = [os.path.join(CSRC, "fq_kernels.hip"), os.path.join(CSRC, "fq_api.cpp")]
+HEADERS = [os.path.join(CSRC, "fq_internal.h"), os.path.join(HERE, "..", "include", "fq.h")]
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+         "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wextra", "-Wno-unused-command-line-argument"]
+
+
+def stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
+
+
+def build(force: bool = True, extra=()) -> str:
+    if not force and not stale():
+        return LIB
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    cmd = [HIPCC, *FLAGS, *extra, "-I", os.path.join(HERE, "..", "include"), *SOURCES, "-o", tmp]
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

@@ -1,0 +1,333 @@
+// Host side of libfq: argument validation, chunk planning, workspace layout and the C ABI
+// declared in include/fq.h.  Validation and sizing are pure host code (no HIP call), so they can
+// be exercised on a machine without a GPU.
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "../../include/fq.h"
+#include "fq_internal.h"
+
+namespace fq {
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr long long kMaxBlocks = 0x7fffffffLL;
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// Partial overlap of [a, a+bytes) and [b, b+bytes) (identical ranges are fine).
+bool partial_overlap(const void *a, const void *b, size_t bytes)
+{
+    if (!a || !b || a == b || bytes == 0) return false;
+    uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
+    return pa < pb ? (pb - pa) < bytes : (pa - pb) < bytes;
+}
+
+struct Plan {
+    long long numel = 0;
+    unsigned slabs = 0, cps = 0, chunk = 0;
+    long long blocks = 0;
+};
+
+// Split every [outer, channel] slab into cps equal chunks of at most kChunkVecs vectors each,
+// chunk length a multiple of the vector width so all chunks of a slab share one alignment.
+fq_status plan_tensor(const fq_tensor &t, Plan &p)
+{
+    if (t.dtype != FQ_F16 && t.dtype != FQ_F32) return FQ_ERR_DTYPE;
+    if (t.outer < 0 || t.channels < 0 || t.inner < 0) return FQ_ERR_SHAPE;
+    if (t.channels > 0x7fffffffLL || t.outer > 0x7fffffffLL) return FQ_ERR_SHAPE;
+    const long long slabs = t.outer * t.channels;
+    if (slabs > 0x7fffffffLL) return FQ_ERR_SHAPE;
+    if (t.inner > 0 && slabs > 0 && t.inner > (1LL << 62) / slabs) return FQ_ERR_SHAPE;
+    p.numel = slabs * t.inner;
+    p.slabs = (unsigned)slabs;
+    if (p.numel == 0) {
+        p.cps = 0; p.chunk = 0; p.blocks = 0;
+        return FQ_OK;
+    }
+    const long long vec = kVecBytes / (t.dtype == FQ_F16 ? 2 : 4);
+    const long long cap = (long long)kChunkVecs * vec;
+    long long cps = (t.inner + cap - 1) / cap;
+    long long chunk = (t.inner + cps - 1) / cps;
+    chunk = (chunk + vec - 1) / vec * vec;
+    cps = (t.inner + chunk - 1) / chunk;
+    if (cps > kMaxBlocks || slabs * cps > kMaxBlocks) return FQ_ERR_SHAPE;
+    p.cps = (unsigned)cps;
+    p.chunk = (unsigned)chunk;
+    p.blocks = slabs * cps;
+    return FQ_OK;
+}
+
+fq_status validate_one(const fq_tensor &t, int mode, Plan &p)
+{
+    fq_status st = plan_tensor(t, p);
+    if (st != FQ_OK) return st;
+    if (!(t.qmin <= 0 && 0 <= t.qmax && t.qmin < t.qmax) || t.qmin < -32768 || t.qmax > 32768)
+        return FQ_ERR_QRANGE;
+    if (!std::isfinite(t.eps) || std::isnan(t.s_min) || std::isnan(t.s_max) || !(t.s_min > 0.0f) ||
+        !std::isfinite(t.s_min) || !(t.s_max >= t.s_min))
+        return FQ_ERR_SCALE_PARAMS;
+    const size_t esz = t.dtype == FQ_F16 ? 2 : 4;
+    const size_t bytes = (size_t)p.numel * esz;
+    if (t.channels > 0 && !t.theta) return FQ_ERR_NULL;
+    if (!aligned(t.theta, 4) || !aligned(t.s, 4) || !aligned(t.gs, 4) || !aligned(t.gtheta, 4))
+        return FQ_ERR_ALIGN;
+    if (p.numel > 0 && !t.x) return FQ_ERR_NULL;
+    if (!aligned(t.x, esz)) return FQ_ERR_ALIGN;
+    if (mode == FQ_MODE_FORWARD) {
+        if (p.numel > 0 && !t.y) return FQ_ERR_NULL;
+        if (!aligned(t.y, esz)) return FQ_ERR_ALIGN;
+        if (t.q && (t.qmin < -128 || t.qmax > 127)) return FQ_ERR_QRANGE;
+        if (partial_overlap(t.x, t.y, bytes)) return FQ_ERR_ALIAS;
+    } else {
+        const bool need_gx = !(t.flags & FQ_FLAG_NO_DX);
+        if (p.numel > 0 && (!t.gy || (need_gx && !t.gx))) return FQ_ERR_NULL;
+        if (!aligned(t.gy, esz) || (need_gx && !aligned(t.gx, esz))) return FQ_ERR_ALIGN;
+        if (need_gx && (partial_overlap(t.gy, t.gx, bytes) || partial_overlap(t.x, t.gx, bytes)))
+            return FQ_ERR_ALIAS;
+    }
+    return FQ_OK;
+}
+
+struct Layout {
+    std::vector<Plan> plans;
+    long long blocks = 0;        // grid of the main kernel
+    long long channels = 0;      // grid of the finalize kernel
+    long long partials = 0;      // floats
+    size_t table_bytes = 0, partial_off = 0, counter_off = 0, total = 0;
+    bool any_empty_with_channels = false;
+};
+
+fq_status make_layout(const fq_tensor *ts, int n, int mode, Layout &L)
+{
+    if (mode != FQ_MODE_FORWARD && mode != FQ_MODE_BACKWARD) return FQ_ERR_SHAPE;
+    if (n < 0) return FQ_ERR_SHAPE;
+    if (n > 0 && !ts) return FQ_ERR_NULL;
+    L.plans.resize((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        fq_status st = validate_one(ts[i], mode, L.plans[(size_t)i]);
+        if (st != FQ_OK) return st;
+        L.blocks += L.plans[(size_t)i].blocks;
+        L.channels += ts[i].channels;
+        if (L.plans[(size_t)i].numel == 0 && ts[i].channels > 0) L.any_empty_with_channels = true;
+        if (L.blocks > kMaxBlocks || L.channels > kMaxBlocks) return FQ_ERR_SHAPE;
+    }
+    L.partials = L.blocks;
+    L.table_bytes = round_up((size_t)n * sizeof(DevTensor), kAlign);
+    L.partial_off = L.table_bytes;
+    L.counter_off = L.partial_off;
+    L.total = L.table_bytes;
+    if (mode == FQ_MODE_BACKWARD) {
+        L.counter_off = L.partial_off + round_up((size_t)L.partials * sizeof(float), kAlign);
+        L.total = L.counter_off + round_up((size_t)L.channels * sizeof(unsigned), kAlign);
+    }
+    if (L.total < kAlign) L.total = kAlign;
+    return FQ_OK;
+}
+
+// Fill the device descriptors; partial/counter pointers are carved out of the workspace.
+void build_table(const fq_tensor *ts, int n, const Layout &L, char *workspace, std::vector<DevTensor> &out)
+{
+    out.resize((size_t)n);
+    long long block = 0, chan = 0;
+    for (int i = 0; i < n; ++i) {
+        const fq_tensor &t = ts[i];
+        const Plan &p = L.plans[(size_t)i];
+        DevTensor &d = out[(size_t)i];
+        std::memset(&d, 0, sizeof d);
+        d.x = t.x; d.y = t.y; d.q = t.q; d.theta = t.theta; d.s = t.s;
+        d.gy = t.gy; d.gx = t.gx; d.gs = t.gs; d.gtheta = t.gtheta;
+        d.partial = workspace ? (float *)(workspace + L.partial_off) + block : nullptr;
+        d.counter = workspace ? (unsigned *)(workspace + L.counter_off) + chan : nullptr;
+        d.inner = t.inner;
+        d.slabs = p.slabs;
+        d.channels = (unsigned)t.channels;
+        d.outer = p.numel ? (unsigned)t.outer : 0u;
+        d.cps = p.cps;
+        d.chunk = p.chunk;
+        d.block_begin = (unsigned)block;
+        d.chan_begin = (unsigned)chan;
+        d.dtype = t.dtype;
+        d.lo = (float)t.qmin;
+        d.hi = (float)t.qmax;
+        d.eps = t.eps; d.s_min = t.s_min; d.s_max = t.s_max;
+        d.flags = t.flags;
+        block += p.blocks;
+        chan += t.channels;
+    }
+}
+
+// Pinned staging slots for the descriptor table of fq_multi_tensor.  The async copy reads the
+// slot after the call has returned, so a slot is reused only once its copy has completed.
+class Staging {
+public:
+    int copy(void *dst, const void *src, size_t bytes, hipStream_t stream)
+    {
+        std::lock_guard<std::mutex> lock(mu_);
+        Slot &s = slots_[next_];
+        next_ = (next_ + 1) % kSlots;
+        hipError_t e;
+        if (s.busy) {
+            if ((e = hipEventSynchronize(s.done)) != hipSuccess) return (int)e;
+            s.busy = false;
+        }
+        if (s.cap < bytes) {
+            if (s.host) (void)hipHostFree(s.host);
+            s.host = nullptr; s.cap = 0;
+            size_t cap = round_up(bytes, 4096);
+            if ((e = hipHostMalloc(&s.host, cap, hipHostMallocDefault)) != hipSuccess) return (int)e;
+            s.cap = cap;
+        }
+        if (!s.done && (e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming)) != hipSuccess)
+            return (int)e;
+        std::memcpy(s.host, src, bytes);
+        if ((e = hipMemcpyAsync(dst, s.host, bytes, hipMemcpyHostToDevice, stream)) != hipSuccess)
+            return (int)e;
+        if ((e = hipEventRecord(s.done, stream)) != hipSuccess) return (int)e;
+        s.busy = true;
+        return 0;
+    }
+
+private:
+    static constexpr int kSlots = 8;
+    struct Slot {
+        void *host = nullptr;
+        size_t cap = 0;
+        hipEvent_t done = nullptr;
+        bool busy = false;
+    };
+    Slot slots_[kSlots];
+    int next_ = 0;
+    std::mutex mu_;
+};
+
+Staging &staging()
+{
+    static Staging *s = new Staging();   // never destroyed: no HIP calls during process teardown
+    return *s;
+}
+
+bool any_flag(const fq_tensor *ts, int n, unsigned flag)
+{
+    for (int i = 0; i < n; ++i)
+        if (ts[i].flags & flag) return true;
+    return false;
+}
+
+fq_status run(const fq_tensor *ts, int n, int mode, bool use_table, void *workspace, size_t ws_bytes,
+              void *stream)
+{
+    Layout L;
+    fq_status st = make_layout(ts, n, mode, L);
+    if (st != FQ_OK) return st;
+    if (n == 0) return FQ_OK;
+    const bool need_ws = use_table || mode == FQ_MODE_BACKWARD;
+    if (need_ws) {
+        if (!workspace || ws_bytes < L.total) return FQ_ERR_WORKSPACE;
+        if (!aligned(workspace, kAlign)) return FQ_ERR_ALIGN;
+    }
+    std::vector<DevTensor> table;
+    build_table(ts, n, L, (char *)workspace, table);
+
+    KArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.n = n;
+    if (use_table) {
+        a.table = (const DevTensor *)workspace;
+        if (copy_table_async(workspace, table.data(), (size_t)n * sizeof(DevTensor), stream) != 0)
+            return FQ_ERR_LAUNCH;
+    } else {
+        a.one = table[0];
+    }
+
+    if (mode == FQ_MODE_FORWARD) {
+        bool emit_q = false;
+        for (int i = 0; i < n; ++i) emit_q = emit_q || ts[i].q != nullptr;
+        if (L.blocks > 0 && launch_forward(a, (unsigned)L.blocks, emit_q, stream) != 0) return FQ_ERR_LAUNCH;
+        // tensors without elements never reach a block: write the scales of all channels in a
+        // separate small launch (same values as the main kernel writes)
+        if (L.any_empty_with_channels && launch_scale_only(a, (unsigned)L.channels, stream) != 0)
+            return FQ_ERR_LAUNCH;
+        return FQ_OK;
+    }
+
+    const bool two_pass = any_flag(ts, n, FQ_FLAG_TWO_PASS) || L.any_empty_with_channels;
+    if (L.blocks > 0 && launch_backward(a, (unsigned)L.blocks, !two_pass, stream) != 0) return FQ_ERR_LAUNCH;
+    if (two_pass && L.channels > 0 && launch_finalize(a, (unsigned)L.channels, stream) != 0)
+        return FQ_ERR_LAUNCH;
+    return FQ_OK;
+}
+
+}  // namespace
+
+int copy_table_async(void *dst_device, const void *src_host, size_t bytes, void *stream)
+{
+    return staging().copy(dst_device, src_host, bytes, (hipStream_t)stream);
+}
+
+}  // namespace fq
+
+extern "C" {
+
+size_t fq_workspace_bytes(const fq_tensor *ts, int n, int mode)
+{
+    fq::Layout L;
+    if (fq::make_layout(ts, n, mode, L) != FQ_OK) return 0;
+    return L.total;
+}
+
+fq_status fq_validate(const fq_tensor *ts, int n, int mode)
+{
+    fq::Layout L;
+    return fq::make_layout(ts, n, mode, L);
+}
+
+fq_status fq_workspace_init(void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    if (!workspace) return FQ_ERR_WORKSPACE;
+    if (!fq::aligned(workspace, 4) || ws_bytes % 4 != 0) return FQ_ERR_ALIGN;
+    return fq::launch_fill_zero(workspace, ws_bytes, hip_stream) == 0 ? FQ_OK : FQ_ERR_LAUNCH;
+}
+
+fq_status fq_forward(const fq_tensor *t, void *hip_stream)
+{
+    if (!t) return FQ_ERR_NULL;
+    return fq::run(t, 1, FQ_MODE_FORWARD, false, nullptr, 0, hip_stream);
+}
+
+fq_status fq_backward(const fq_tensor *t, void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    if (!t) return FQ_ERR_NULL;
+    return fq::run(t, 1, FQ_MODE_BACKWARD, false, workspace, ws_bytes, hip_stream);
+}
+
+fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,
+                          void *hip_stream)
+{
+    return fq::run(ts, n, mode, true, workspace, ws_bytes, hip_stream);
+}
+
+const char *fq_status_string(fq_status status)
+{
+    switch (status) {
+    case FQ_OK: return "ok";
+    case FQ_ERR_NULL: return "a required pointer is NULL";
+    case FQ_ERR_DTYPE: return "dtype must be FQ_F16 or FQ_F32";
+    case FQ_ERR_SHAPE: return "bad extent, count, n or mode";
+    case FQ_ERR_QRANGE: return "bad integer code range";
+    case FQ_ERR_ALIGN: return "pointer not aligned";
+    case FQ_ERR_WORKSPACE: return "workspace missing or too small";
+    case FQ_ERR_SCALE_PARAMS: return "bad eps / s_min / s_max";
+    case FQ_ERR_LAUNCH: return "HIP runtime error while enqueuing";
+    case FQ_ERR_ALIAS: return "output partially overlaps an input";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,55 @@
+// Internal interface between the host-side planner (fq_api.cpp) and the gfx950 kernels
+// (fq_kernels.hip).  Not part of the C ABI.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace fq {
+
+constexpr int kBlock = 256;          // threads per block: four 64-wide wavefronts
+constexpr int kVecBytes = 16;        // one 128-bit global load/store per lane
+constexpr int kChunkVecs = 1024;     // at most this many 128-bit vectors per block (16 KiB)
+
+// Device-side view of one tensor.  Built on the host; passed as a kernel argument for
+// single-tensor calls, or as an array in device memory for the multi-tensor launch.
+struct DevTensor {
+    const void *x;
+    void *y;
+    int8_t *q;
+    const float *theta;
+    float *s;
+    const void *gy;
+    void *gx;
+    float *gs;
+    float *gtheta;
+    float *partial;            // [slabs * cps] per-block partial sums of gy*t (backward)
+    unsigned *counter;         // [channels] arrival tickets, zero between calls (backward)
+    long long inner;           // elements per slab
+    unsigned slabs;            // outer * channels
+    unsigned channels;
+    unsigned outer;
+    unsigned cps;              // chunks per slab
+    unsigned chunk;            // elements per chunk, a multiple of the vector width
+    unsigned block_begin;      // first block of this tensor in the grid
+    unsigned chan_begin;       // first channel of this tensor in the finalize grid
+    int dtype;                 // 0 = FP16, 1 = FP32
+    float lo, hi;              // (float)qmin, (float)qmax
+    float eps, s_min, s_max;
+    unsigned flags;
+};
+
+struct KArgs {
+    DevTensor one;             // used when table == nullptr
+    const DevTensor *table;    // device array of n descriptors (multi-tensor launch)
+    int n;
+};
+
+// Launchers; each returns the hipError_t value as int (0 = success).
+int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream);
+int launch_backward(const KArgs &a, unsigned blocks, bool fused_finalize, void *stream);
+int launch_finalize(const KArgs &a, unsigned total_channels, void *stream);
+int launch_scale_only(const KArgs &a, unsigned total_channels, void *stream);
+int launch_fill_zero(void *p, size_t bytes, void *stream);
+int copy_table_async(void *dst_device, const void *src_host, size_t bytes, void *stream);
+
+}  // namespace fq

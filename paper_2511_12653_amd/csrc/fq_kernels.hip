@@ -1,0 +1,492 @@
+// gfx950 kernels for fused learnable-scale fake quantization (DPVO-QAT++ Sec. 3.2, Eq. (3)-(6),
+// and the straight-through backward stated next to Eq. (5)).
+//
+// The work is HBM-bound elementwise traffic plus one per-channel reduction, so there is no MFMA
+// here.  Each 256-thread block owns one chunk (at most 16 KiB of input) that lies inside a single
+// [outer, channel] slab, so the scale is uniform over the block; lanes move 128-bit vectors
+// (global_load/store_dwordx4), FP16 is widened/narrowed in registers.  Backward adds a DPP
+// wavefront reduction, an LDS block reduction, one partial sum per block, and a fixed-order final
+// sum per channel carried out by whichever block of that channel finishes last.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fq_internal.h"
+
+namespace fq {
+
+namespace {
+
+template <typename T> struct VecOf;
+template <> struct VecOf<float> {
+    static constexpr int N = 4;
+    typedef float type __attribute__((ext_vector_type(4)));
+};
+template <> struct VecOf<_Float16> {
+    static constexpr int N = 8;
+    typedef _Float16 type __attribute__((ext_vector_type(8)));
+};
+
+constexpr int kUnroll = kChunkVecs / kBlock;   // vectors per thread per chunk
+static_assert(kChunkVecs % kBlock == 0, "chunk must be a whole number of block-wide vector rows");
+
+// ---------------------------------------------------------------------------------------------
+// Eq. (3)-(4): s = clip(softplus(theta) + eps, s_min, s_max).  Evaluated in binary64 and rounded
+// to binary32 once, so the value does not depend on the accuracy of a binary32 exp/log.
+// clip_active: the clamp changed the value (its derivative is then zero).
+struct Scale {
+    float s;
+    bool clip_active;
+};
+
+__device__ inline Scale compute_scale(float theta, float eps, float s_min, float s_max)
+{
+    double t = (double)theta;
+    double u = fmax(t, 0.0) + log1p(exp(-fabs(t))) + (double)eps;
+    float uf = (float)u;
+    Scale r;
+    r.clip_active = !(uf >= s_min && uf <= s_max);
+    float v = uf;
+    v = v < s_min ? s_min : v;
+    v = v > s_max ? s_max : v;
+    r.s = v;
+    return r;
+}
+
+__device__ inline double sigmoid64(double t)
+{
+    if (t >= 0.0) return 1.0 / (1.0 + exp(-t));
+    double e = exp(t);
+    return e / (1.0 + e);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per-element arithmetic.  The quotient is the correctly rounded binary32 x/s (hipcc's default
+// IEEE division); clip passes NaN through (comparisons are false), rint is v_rndne_f32.
+__device__ __forceinline__ float quotient(float x, float s) { return x / s; }
+
+__device__ __forceinline__ float clip_keep_nan(float v, float lo, float hi)
+{
+    v = v < lo ? lo : v;
+    v = v > hi ? hi : v;
+    return v;
+}
+
+struct QParams {
+    float s, lo, hi;
+};
+
+// forward value; qf receives the integer-valued code (NaN for NaN input)
+__device__ __forceinline__ float fq_value(float x, const QParams &p, float &qf)
+{
+    float v = quotient(x, p.s);
+    qf = __builtin_rintf(clip_keep_nan(v, p.lo, p.hi));
+    return qf * p.s;
+}
+
+__device__ __forceinline__ int8_t code_of(float qf) { return qf != qf ? (int8_t)0 : (int8_t)(int)qf; }
+
+// backward: returns t = dy/ds and whether the quotient is inside [lo, hi] (inclusive)
+__device__ __forceinline__ float ste_terms(float x, const QParams &p, bool &in_range)
+{
+    float v = quotient(x, p.s);
+    in_range = (v >= p.lo) && (v <= p.hi);
+    float outside = v < p.lo ? p.lo : (v > p.hi ? p.hi : v);   // NaN stays NaN
+    return in_range ? (__builtin_rintf(v) - v) : outside;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Reductions.  DPP inside rows of 16 lanes, cross-row exchange for the last two steps; every lane
+// ends with the same sum and the order of additions is fixed.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v)
+{
+    int i = __builtin_bit_cast(int, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, i, CTRL, 0xf, 0xf, false));
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);   // row_half_mirror
+    v += dpp_move<0x140>(v);   // row_mirror
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Chunk addressing shared by forward and backward.
+struct Chunk {
+    unsigned slab, channel;
+    long long first;   // flat element index of the chunk's first element
+    int n;             // elements in the chunk
+};
+
+__device__ __forceinline__ Chunk locate_chunk(const DevTensor &d, unsigned local_block)
+{
+    Chunk c;
+    c.slab = local_block / d.cps;
+    unsigned k = local_block - c.slab * d.cps;
+    c.channel = c.slab % d.channels;
+    long long e0 = (long long)k * d.chunk;
+    long long rem = d.inner - e0;
+    c.n = rem < (long long)d.chunk ? (int)rem : (int)d.chunk;
+    c.first = (long long)c.slab * d.inner + e0;
+    return c;
+}
+
+// elements before the first 16-byte boundary of p
+template <typename T> __device__ __forceinline__ int head_elems(const void *p, int n)
+{
+    int h = (int)(((kVecBytes - ((uintptr_t)p & (kVecBytes - 1))) & (kVecBytes - 1)) / sizeof(T));
+    return h < n ? h : n;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward.
+template <typename T, bool EMIT_Q>
+__device__ __forceinline__ void forward_elem(const T *x, T *y, int8_t *q, int i, const QParams &p)
+{
+    float qf;
+    float yf = fq_value((float)x[i], p, qf);
+    y[i] = (T)yf;
+    if (EMIT_Q && q) q[i] = code_of(qf);
+}
+
+template <typename T, bool EMIT_Q>
+__device__ void forward_chunk(const DevTensor &d, unsigned local_block)
+{
+    typedef typename VecOf<T>::type VT;
+    constexpr int N = VecOf<T>::N;
+    const Chunk ck = locate_chunk(d, local_block);
+    const T *x = (const T *)d.x + ck.first;
+    T *y = (T *)d.y + ck.first;
+    int8_t *q = (EMIT_Q && d.q) ? d.q + ck.first : nullptr;
+    const int tid = threadIdx.x;
+
+    const bool vector_ok = (((uintptr_t)x ^ (uintptr_t)y) & (kVecBytes - 1)) == 0;
+    const int head = vector_ok ? head_elems<T>(x, ck.n) : ck.n;
+    const int nvec = (ck.n - head) / N;
+    const VT *xv = (const VT *)(x + head);
+    VT *yv = (VT *)(y + head);
+
+    // issue the first row of loads before the (long, binary64) scale evaluation
+    VT r[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        int v = u * kBlock + tid;
+        if (v < nvec) r[u] = xv[v];
+    }
+
+    const Scale sc = compute_scale(d.theta[ck.channel], d.eps, d.s_min, d.s_max);
+    const QParams p = {sc.s, d.lo, d.hi};
+    if (d.s && ck.first == (long long)ck.channel * d.inner && tid == 0) d.s[ck.channel] = sc.s;
+
+    for (int v0 = 0;;) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int v = v0 + u * kBlock + tid;
+            if (v < nvec) {
+                VT o;
+                float qf[N];
+#pragma unroll
+                for (int e = 0; e < N; ++e) o[e] = (T)fq_value((float)r[u][e], p, qf[e]);
+                yv[v] = o;
+                if (EMIT_Q && q) {
+#pragma unroll
+                    for (int e = 0; e < N; ++e) q[head + v * N + e] = code_of(qf[e]);
+                }
+            }
+        }
+        v0 += kUnroll * kBlock;
+        if (v0 >= nvec) break;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int v = v0 + u * kBlock + tid;
+            if (v < nvec) r[u] = xv[v];
+        }
+    }
+
+    // scalar head (before the first 16-byte boundary, or the whole chunk if x and y are
+    // misaligned relative to each other) and tail (after the last whole vector)
+    for (int i = tid; i < head; i += kBlock) forward_elem<T, EMIT_Q>(x, y, q, i, p);
+    for (int i = head + nvec * N + tid; i < ck.n; i += kBlock) forward_elem<T, EMIT_Q>(x, y, q, i, p);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward.
+template <typename T, bool WRITE_GX>
+__device__ __forceinline__ float backward_elem(const T *x, const T *gy, T *gx, int i, const QParams &p)
+{
+    bool in_range;
+    T g = gy[i];
+    float t = ste_terms((float)x[i], p, in_range);
+    if (WRITE_GX) gx[i] = in_range ? g : (T)0.0f;
+    return (float)g * t;
+}
+
+// Per-thread sum of gy*t over this thread's elements of the chunk (binary32).
+template <typename T, bool WRITE_GX>
+__device__ float backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_out)
+{
+    typedef typename VecOf<T>::type VT;
+    constexpr int N = VecOf<T>::N;
+    const T *x = (const T *)d.x + ck.first;
+    const T *gy = (const T *)d.gy + ck.first;
+    T *gx = WRITE_GX ? (T *)d.gx + ck.first : nullptr;
+    const int tid = threadIdx.x;
+
+    uintptr_t mis = (uintptr_t)x ^ (uintptr_t)gy;
+    if (WRITE_GX) mis |= (uintptr_t)x ^ (uintptr_t)gx;
+    const bool vector_ok = (mis & (kVecBytes - 1)) == 0;
+    const int head = vector_ok ? head_elems<T>(x, ck.n) : ck.n;
+    const int nvec = (ck.n - head) / N;
+    const VT *xv = (const VT *)(x + head);
+    const VT *gv = (const VT *)(gy + head);
+    VT *ov = WRITE_GX ? (VT *)(gx + head) : nullptr;
+
+    VT rx[kUnroll], rg[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        int v = u * kBlock + tid;
+        if (v < nvec) {
+            rx[u] = xv[v];
+            rg[u] = gv[v];
+        }
+    }
+
+    const Scale sc = compute_scale(d.theta[ck.channel], d.eps, d.s_min, d.s_max);
+    sc_out = sc;
+    const QParams p = {sc.s, d.lo, d.hi};
+
+    float acc[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) acc[u] = 0.0f;
+
+    for (int v0 = 0;;) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int v = v0 + u * kBlock + tid;
+            if (v < nvec) {
+                VT o;
+#pragma unroll
+                for (int e = 0; e < N; ++e) {
+                    bool in_range;
+                    float t = ste_terms((float)rx[u][e], p, in_range);
+                    o[e] = in_range ? rg[u][e] : (T)0.0f;
+                    acc[u] = __builtin_fmaf((float)rg[u][e], t, acc[u]);
+                }
+                if (WRITE_GX) ov[v] = o;
+            }
+        }
+        v0 += kUnroll * kBlock;
+        if (v0 >= nvec) break;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int v = v0 + u * kBlock + tid;
+            if (v < nvec) {
+                rx[u] = xv[v];
+                rg[u] = gv[v];
+            }
+        }
+    }
+
+    float sum = 0.0f;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) sum += acc[u];
+    for (int i = tid; i < head; i += kBlock) sum += backward_elem<T, WRITE_GX>(x, gy, gx, i, p);
+    for (int i = head + nvec * N + tid; i < ck.n; i += kBlock)
+        sum += backward_elem<T, WRITE_GX>(x, gy, gx, i, p);
+    return sum;
+}
+
+// Sum the per-block partials of channel c in a fixed order (thread-strided binary64 sums, fixed
+// tree) and apply the chain rule through Eq. (3)-(4).  Block-wide; lds holds kBlock/64 doubles.
+__device__ void finalize_channel(const DevTensor &d, unsigned c, double *lds)
+{
+    const unsigned bpc = d.outer * d.cps;
+    double acc = 0.0;
+    for (unsigned j = threadIdx.x; j < bpc; j += kBlock) {
+        unsigned o = j / d.cps;
+        unsigned k = j - o * d.cps;
+        size_t idx = ((size_t)o * d.channels + c) * d.cps + k;
+        // agent-scope load: the partial may have been written by a block on another XCD
+        acc += (double)__hip_atomic_load(&d.partial[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double total = 0.0;
+#pragma unroll
+        for (int w = 0; w < kBlock / 64; ++w) total += lds[w];
+        const float theta = d.theta[c];
+        const Scale sc = compute_scale(theta, d.eps, d.s_min, d.s_max);
+        if (d.gs) d.gs[c] = (float)total;
+        if (d.gtheta) d.gtheta[c] = sc.clip_active ? 0.0f : (float)(total * sigmoid64((double)theta));
+        if (d.s) d.s[c] = sc.s;
+    }
+    __syncthreads();
+}
+
+template <bool FUSED>
+__device__ void backward_block(const DevTensor &d, unsigned local_block)
+{
+    __shared__ float wave_part[kBlock / 64];
+    __shared__ double fin_part[kBlock / 64];
+    __shared__ unsigned is_last;
+
+    const Chunk ck = locate_chunk(d, local_block);
+    const bool write_gx = !(d.flags & 1u);
+    Scale sc;
+    float sum;
+    if (d.dtype == 0)
+        sum = write_gx ? backward_chunk<_Float16, true>(d, ck, sc) : backward_chunk<_Float16, false>(d, ck, sc);
+    else
+        sum = write_gx ? backward_chunk<float, true>(d, ck, sc) : backward_chunk<float, false>(d, ck, sc);
+
+    sum = wave_sum(sum);
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float total = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kBlock / 64; ++w) total += wave_part[w];
+        __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (FUSED) {
+            const unsigned bpc = d.outer * d.cps;
+            // release our partial, take a ticket; the block that draws the last ticket of this
+            // channel sees every other block's partial after its acquire
+            unsigned ticket = __hip_atomic_fetch_add(&d.counter[ck.channel], 1u, __ATOMIC_ACQ_REL,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+            unsigned last = (ticket == bpc - 1u) ? 1u : 0u;
+            if (last)   // leave the counter at zero for the next call
+                __hip_atomic_store(&d.counter[ck.channel], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            is_last = last;
+        }
+    }
+    if (FUSED) {
+        __syncthreads();
+        if (is_last) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            finalize_channel(d, ck.channel, fin_part);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Block -> tensor lookup for the multi-tensor grid: last tensor whose first block is <= block.
+__device__ __forceinline__ int find_by_block(const DevTensor *table, int n, unsigned block)
+{
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (table[mid].block_begin <= block) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ int find_by_channel(const DevTensor *table, int n, unsigned chan)
+{
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (table[mid].chan_begin <= chan) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+template <bool EMIT_Q>
+__global__ void __launch_bounds__(kBlock) forward_kernel(const KArgs a)
+{
+    const DevTensor *dp = a.table ? &a.table[find_by_block(a.table, a.n, blockIdx.x)] : &a.one;
+    const DevTensor &d = *dp;
+    const unsigned local = blockIdx.x - d.block_begin;
+    if (d.dtype == 0) forward_chunk<_Float16, EMIT_Q>(d, local);
+    else forward_chunk<float, EMIT_Q>(d, local);
+}
+
+template <bool FUSED>
+__global__ void __launch_bounds__(kBlock) backward_kernel(const KArgs a)
+{
+    const DevTensor *dp = a.table ? &a.table[find_by_block(a.table, a.n, blockIdx.x)] : &a.one;
+    backward_block<FUSED>(*dp, blockIdx.x - dp->block_begin);
+}
+
+// one block per channel: second pass of the two-pass backward, and the whole backward of tensors
+// that have channels but no elements (their gradients are zero)
+__global__ void __launch_bounds__(kBlock) finalize_kernel(const KArgs a)
+{
+    __shared__ double fin_part[kBlock / 64];
+    const DevTensor *dp = a.table ? &a.table[find_by_channel(a.table, a.n, blockIdx.x)] : &a.one;
+    finalize_channel(*dp, blockIdx.x - dp->chan_begin, fin_part);
+}
+
+// s[c] for every channel; used when a tensor has channels but no elements (forward)
+__global__ void __launch_bounds__(kBlock) scale_kernel(const KArgs a, unsigned total_channels)
+{
+    unsigned g = blockIdx.x * kBlock + threadIdx.x;
+    if (g >= total_channels) return;
+    const DevTensor *dp = a.table ? &a.table[find_by_channel(a.table, a.n, g)] : &a.one;
+    unsigned c = g - dp->chan_begin;
+    if (dp->s) dp->s[c] = compute_scale(dp->theta[c], dp->eps, dp->s_min, dp->s_max).s;
+}
+
+__global__ void __launch_bounds__(kBlock) fill_zero_kernel(unsigned *p, size_t words)
+{
+    size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (; i < words; i += stride) p[i] = 0u;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    if (emit_q) hipLaunchKernelGGL(forward_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, a);
+    else hipLaunchKernelGGL(forward_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, a);
+    return (int)hipGetLastError();
+}
+
+int launch_backward(const KArgs &a, unsigned blocks, bool fused_finalize, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    if (fused_finalize) hipLaunchKernelGGL(backward_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, a);
+    else hipLaunchKernelGGL(backward_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, a);
+    return (int)hipGetLastError();
+}
+
+int launch_finalize(const KArgs &a, unsigned total_channels, void *stream)
+{
+    hipLaunchKernelGGL(finalize_kernel, dim3(total_channels), dim3(kBlock), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+int launch_scale_only(const KArgs &a, unsigned total_channels, void *stream)
+{
+    unsigned blocks = (total_channels + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(kBlock), 0, (hipStream_t)stream, a, total_channels);
+    return (int)hipGetLastError();
+}
+
+int launch_fill_zero(void *p, size_t bytes, void *stream)
+{
+    size_t words = bytes / 4;
+    if (words == 0) return 0;
+    size_t want = (words + kBlock - 1) / kBlock;
+    unsigned blocks = (unsigned)(want < 4096 ? want : 4096);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(kBlock), 0, (hipStream_t)stream,
+                       (unsigned *)p, words);
+    return (int)hipGetLastError();
+}
+
+}  // namespace fq

@@ -1,0 +1,114 @@
+"""Host-side logic of the C ABI: the library loads, exports every declared symbol, and its
+pure-host validation / workspace sizing behave as include/fq.h says.  No GPU call is made."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def fq():
+    from paper_2511_12653_amd import build
+    if build.stale():
+        build.build()
+    from paper_2511_12653_amd import binding
+    return binding
+
+
+def test_exports_every_declared_symbol(fq):
+    hdr = open(os.path.join(ROOT, "include", "fq.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = re.findall(r"\b(fq_[a-z_]+)\s*\(", hdr)
+    assert set(names) >= {"fq_forward", "fq_backward", "fq_multi_tensor", "fq_workspace_bytes",
+                          "fq_validate", "fq_status_string", "fq_workspace_init"}
+    lib = ctypes.CDLL(fq.library_path())
+    for n in set(names):
+        assert getattr(lib, n) is not None
+
+
+def test_struct_size_matches_header(fq):
+    # 3*8 + 3*4 + 3*4 + 4 (flags) = 52 -> padded to 56, then 9 pointers
+    assert ctypes.sizeof(fq.FqTensor) == 56 + 9 * 8
+
+
+def _desc(fq, **kw):
+    base = dict(outer=2, channels=3, inner=100, dtype=fq.FQ_F16, qmin=-128, qmax=127, eps=0.0,
+                s_min=fq.FLT_MIN, s_max=float("inf"), flags=0, x=0x10000, y=0x20000, q=None,
+                theta=0x30000, s=None, gy=0x40000, gx=0x50000, gs=None, gtheta=0x60000)
+    base.update(kw)
+    return fq.FqTensor(**base)
+
+
+def test_validate_ok_and_status_strings(fq):
+    assert fq.fq_validate(_desc(fq), fq.FQ_MODE_FORWARD) == 0
+    assert fq.fq_validate(_desc(fq), fq.FQ_MODE_BACKWARD) == 0
+    assert fq.fq_status_string(0) == "ok"
+    for code in range(-9, 0):
+        assert fq.fq_status_string(code) not in ("ok", "unknown status")
+    assert fq.fq_status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("kw,mode,code", [
+    (dict(x=None), 1, -1), (dict(y=None), 1, -1), (dict(theta=None), 1, -1),
+    (dict(gy=None), 2, -1), (dict(gx=None), 2, -1),
+    (dict(dtype=7), 1, -2),
+    (dict(outer=-1), 1, -3), (dict(inner=1 << 62, outer=4), 1, -3), (dict(outer=1 << 31), 1, -3),
+    (dict(qmin=1), 1, -4), (dict(qmin=0, qmax=0), 1, -4), (dict(qmax=40000), 1, -4),
+    (dict(q=0x70000, qmin=-129), 1, -4), (dict(q=0x70000, qmax=128), 1, -4),
+    (dict(x=0x10001), 1, -5), (dict(theta=0x30002), 1, -5), (dict(dtype=1, y=0x20002), 1, -5),
+    (dict(gx=0x50001), 2, -5),
+    (dict(s_min=0.0), 1, -7), (dict(s_min=1.0, s_max=0.5), 1, -7), (dict(eps=float("nan")), 1, -7),
+    (dict(eps=float("inf")), 1, -7), (dict(s_min=float("nan")), 1, -7),
+    (dict(y=0x10010), 1, -9), (dict(gx=0x40010), 2, -9),
+])
+def test_validate_errors(fq, kw, mode, code):
+    assert fq.fq_validate(_desc(fq, **kw), mode) == code
+    assert fq.fq_workspace_bytes(_desc(fq, **kw), mode) == 0
+
+
+def test_validate_accepts_edge_cases(fq):
+    assert fq.fq_validate(_desc(fq, y=0x10000), 1) == 0                       # exact in-place
+    assert fq.fq_validate(_desc(fq, gx=0x40000), 2) == 0
+    assert fq.fq_validate(_desc(fq, gx=None, flags=fq.FQ_FLAG_NO_DX), 2) == 0
+    assert fq.fq_validate(_desc(fq, outer=0, x=None, y=None), 1) == 0          # empty tensor
+    assert fq.fq_validate(_desc(fq, channels=0, theta=None, x=None, y=None), 1) == 0
+    assert fq.fq_validate(_desc(fq, qmin=-8, qmax=7), 1) == 0
+    assert fq.fq_validate(_desc(fq, qmin=-127, qmax=127, q=0x70000), 1) == 0
+    assert fq.fq_validate(_desc(fq, x=0x10002), 1) == 0                        # 2-byte aligned FP16
+    assert fq.fq_validate([], 1) == 0
+    # bad mode / list errors
+    assert fq.fq_validate(_desc(fq), 3) == -3
+    assert fq.fq_validate([_desc(fq), _desc(fq, dtype=9)], 1) == -2
+
+
+def test_workspace_bytes(fq):
+    import paper_2511_12653_amd.binding as b
+    t = _desc(fq, outer=15, channels=128, inner=19200, x=1 << 32, y=2 << 32, gy=3 << 32, gx=4 << 32)                # FP16: 8 elems / vector
+    # 19200 elements = 2400 vectors -> 3 chunks per slab -> 5760 blocks, one float each
+    fwd = fq.fq_workspace_bytes(t, 1)
+    bwd = fq.fq_workspace_bytes(t, 2)
+    assert fwd % 256 == 0 and bwd % 256 == 0 and fwd >= 256
+    assert bwd >= fwd + 5760 * 4 + 128 * 4
+    assert bwd <= fwd + 5760 * 4 + 128 * 4 + 3 * 256
+    two = fq.fq_workspace_bytes([t, t], 2)
+    assert two >= 2 * (5760 * 4 + 128 * 4)
+    assert fq.fq_workspace_bytes([], 2) == 256
+    # launching calls refuse a missing or short workspace before touching the GPU
+    with pytest.raises(b.FqError) as e:
+        b.fq_backward(t, None, stream=0)
+    assert e.value.status == -6
+    with pytest.raises(b.FqError) as e:
+        b.fq_backward(t, (0x100000, bwd - 256), stream=0)
+    assert e.value.status == -6
+    with pytest.raises(b.FqError) as e:
+        b.fq_backward(t, (0x100010, bwd), stream=0)
+    assert e.value.status == -5
+    with pytest.raises(b.FqError) as e:
+        b.fq_multi_tensor([t], 1, None, stream=0)
+    assert e.value.status == -6
+    with pytest.raises(b.FqError) as e:
+        b.fq_forward(_desc(fq, x=None), stream=0)
+    assert e.value.status == -1

@@ -1,0 +1,76 @@
+"""GPU parity of fq_multi_tensor: a whole list of tensors in one launch."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_12653_amd import workloads
+from paper_2511_12653_amd import binding as fq
+
+import _gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_list(cases, label, flags=0, want_q=True):
+    H.say("%s: %d tensors, %.1f MiB of inputs, flags=%d" % (
+        label, len(cases), sum(c.x.nbytes for c in cases) / 2 ** 20, flags))
+    dcs = [H.DeviceCase(c, want_q=want_q and c.qmin >= -128, flags=flags) for c in cases]
+    descs = [d.desc for d in dcs]
+    ws = H.workspace_for(descs, fq.FQ_MODE_BACKWARD)
+    assert fq.fq_workspace_bytes(descs, fq.FQ_MODE_FORWARD) <= ws.numel() * 4
+    fq.fq_multi_tensor(descs, fq.FQ_MODE_FORWARD, ws)
+    fq.fq_multi_tensor(descs, fq.FQ_MODE_BACKWARD, ws)
+    torch.cuda.synchronize()
+    for i, (c, d) in enumerate(zip(cases, dcs)):
+        ref = H.oracle_forward(c)
+        H.check_forward(d, ref, "%s[%d] fwd" % (label, i))
+        H.check_backward(d, ref[0], ref[1], "%s[%d] bwd" % (label, i),
+                         want_gx=not (flags & fq.FQ_FLAG_NO_DX))
+        if i % 8 == 7:
+            H.say("%s: %d of %d tensors match" % (label, i + 1, len(cases)))
+    return dcs, ws
+
+
+@pytest.mark.parametrize("flags", [0, fq.FQ_FLAG_TWO_PASS])
+def test_small_mixed_list(flags):
+    cases = workloads.multi_tensor_mixed(n_act=10, n_wgt=6, target_bytes=24 << 20, max_batch=2)
+    _run_list(cases, "multi/small", flags=flags)
+
+
+def test_list_with_empty_and_tiny_members():
+    rng = np.random.default_rng(4)
+    cases = workloads.multi_tensor_mixed(n_act=3, n_wgt=2, target_bytes=4 << 20, max_batch=1)
+    x1 = rng.standard_normal((1, 1, 1)).astype(np.float32)
+    tiny = workloads.TensorCase("tiny", (1,), 1, 1, 1, -8, 7, x1, np.array([0.1], np.float32), x1.copy())
+    empty = workloads.TensorCase("empty", (0, 4, 9), 0, 4, 9, -128, 127, np.zeros((0, 4, 9), np.float16),
+                                 np.array([0.1, 0.2, 0.3, 0.4], np.float32),
+                                 np.zeros((0, 4, 9), np.float16))
+    lst = [empty, cases[0], tiny, cases[1], empty, cases[2], cases[3], cases[4], empty]
+    dcs, _ = _run_list(lst, "multi/empty_members")
+    for d in (dcs[0], dcs[4], dcs[8]):
+        assert torch.all(d.gs == 0) and torch.all(d.gtheta == 0)
+
+
+def test_multi_equals_single_calls_bitwise():
+    cases = workloads.multi_tensor_mixed(n_act=6, n_wgt=4, target_bytes=12 << 20, max_batch=2)
+    dcs, _ = _run_list(cases, "multi/vs_single", want_q=False)
+    H.say("multi/vs_single: single-tensor calls")
+    for c, d in zip(cases, dcs):
+        one = H.DeviceCase(c, want_q=False)
+        fq.fq_forward(one.desc)
+        ws = H.workspace_for(one.desc, fq.FQ_MODE_BACKWARD)
+        fq.fq_backward(one.desc, ws)
+        torch.cuda.synchronize()
+        for name in ("y", "gx", "gs", "gtheta", "s"):
+            a, b = getattr(one, name), getattr(d, name)
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), name
+
+
+@pytest.mark.timeout(600)
+def test_full_size_list_about_1GiB():
+    """The 64-tensor, ~1 GiB list in the launch configuration used for timing: one forward launch
+    and one backward launch, every element checked against the oracle."""
+    cases = workloads.make("multi_tensor_mixed")
+    total = sum(c.x.nbytes for c in cases)
+    assert len(cases) == 64 and abs(total - 2 ** 30) <= 0.05 * 2 ** 30
+    _run_list(cases, "multi/full", want_q=False)
