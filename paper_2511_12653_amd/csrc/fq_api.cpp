@@ -99,7 +99,7 @@ struct Layout {
     std::vector<Plan> plans;
     long long blocks = 0;        // grid of the main kernel
     long long channels = 0;      // grid of the finalize kernel
-    long long partials = 0;      // floats
+    long long partials = 0;      // doubles
     size_t table_bytes = 0, partial_off = 0, counter_off = 0, total = 0;
     bool any_empty_with_channels = false;
 };
@@ -124,7 +124,7 @@ fq_status make_layout(const fq_tensor *ts, int n, int mode, Layout &L)
     L.counter_off = L.partial_off;
     L.total = L.table_bytes;
     if (mode == FQ_MODE_BACKWARD) {
-        L.counter_off = L.partial_off + round_up((size_t)L.partials * sizeof(float), kAlign);
+        L.counter_off = L.partial_off + round_up((size_t)L.partials * sizeof(double), kAlign);
         L.total = L.counter_off + round_up((size_t)L.channels * sizeof(unsigned), kAlign);
     }
     if (L.total < kAlign) L.total = kAlign;
@@ -143,7 +143,7 @@ void build_table(const fq_tensor *ts, int n, const Layout &L, char *workspace, s
         std::memset(&d, 0, sizeof d);
         d.x = t.x; d.y = t.y; d.q = t.q; d.theta = t.theta; d.s = t.s;
         d.gy = t.gy; d.gx = t.gx; d.gs = t.gs; d.gtheta = t.gtheta;
-        d.partial = workspace ? (float *)(workspace + L.partial_off) + block : nullptr;
+        d.partial = workspace ? (double *)(workspace + L.partial_off) + block : nullptr;
         d.counter = workspace ? (unsigned *)(workspace + L.counter_off) + chan : nullptr;
         d.inner = t.inner;
         d.slabs = p.slabs;

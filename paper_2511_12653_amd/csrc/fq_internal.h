@@ -22,7 +22,7 @@ struct DevTensor {
     void *gx;
     float *gs;
     float *gtheta;
-    float *partial;            // [slabs * cps] per-block partial sums of gy*t (backward)
+    double *partial;           // [slabs * cps] per-block partial sums of gy*t (backward)
     unsigned *counter;         // [channels] arrival tickets, zero between calls (backward)
     long long inner;           // elements per slab
     unsigned slabs;            // outer * channels

@@ -95,15 +95,19 @@ __device__ __forceinline__ float ste_terms(float x, const QParams &p, bool &in_r
 }
 
 // ---------------------------------------------------------------------------------------------
-// Reductions.  DPP inside rows of 16 lanes, cross-row exchange for the last two steps; every lane
-// ends with the same sum and the order of additions is fixed.
-template <int CTRL> __device__ __forceinline__ float dpp_move(float v)
+// Reductions.  DPP inside rows of 16 lanes (a binary64 value moves as its two 32-bit halves),
+// cross-row exchange for the last two steps; every lane ends with the same sum and the order of
+// additions is fixed.
+template <int CTRL> __device__ __forceinline__ double dpp_move(double v)
 {
-    int i = __builtin_bit_cast(int, v);
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, i, CTRL, 0xf, 0xf, false));
+    typedef int i32x2 __attribute__((ext_vector_type(2)));
+    i32x2 w = __builtin_bit_cast(i32x2, v);
+    w[0] = __builtin_amdgcn_update_dpp(0, w[0], CTRL, 0xf, 0xf, false);
+    w[1] = __builtin_amdgcn_update_dpp(0, w[1], CTRL, 0xf, 0xf, false);
+    return __builtin_bit_cast(double, w);
 }
 
-__device__ __forceinline__ float wave_sum(float v)
+__device__ __forceinline__ double wave_sum(double v)
 {
     v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
     v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
@@ -111,13 +115,6 @@ __device__ __forceinline__ float wave_sum(float v)
     v += dpp_move<0x140>(v);   // row_mirror
     v += __shfl_xor(v, 16, 64);
     v += __shfl_xor(v, 32, 64);
-    return v;
-}
-
-__device__ __forceinline__ double wave_sum(double v)
-{
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
     return v;
 }
 
@@ -222,19 +219,22 @@ __device__ void forward_chunk(const DevTensor &d, unsigned local_block)
 
 // ---------------------------------------------------------------------------------------------
 // Backward.
+// gy*t is exact in binary64 (two 24-bit significands), so the per-channel sum differs from a
+// sequential binary64 sum only by binary64 rounding, however badly the terms cancel.
 template <typename T, bool WRITE_GX>
-__device__ __forceinline__ float backward_elem(const T *x, const T *gy, T *gx, int i, const QParams &p)
+__device__ __forceinline__ double backward_elem(const T *x, const T *gy, T *gx, int i, const QParams &p,
+                                                double acc)
 {
     bool in_range;
     T g = gy[i];
     float t = ste_terms((float)x[i], p, in_range);
     if (WRITE_GX) gx[i] = in_range ? g : (T)0.0f;
-    return (float)g * t;
+    return __builtin_fma((double)(float)g, (double)t, acc);
 }
 
-// Per-thread sum of gy*t over this thread's elements of the chunk (binary32).
+// Per-thread sum of gy*t over this thread's elements of the chunk (binary64).
 template <typename T, bool WRITE_GX>
-__device__ float backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_out)
+__device__ double backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_out)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
@@ -266,9 +266,9 @@ __device__ float backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_o
     sc_out = sc;
     const QParams p = {sc.s, d.lo, d.hi};
 
-    float acc[kUnroll];
+    double acc[kUnroll];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) acc[u] = 0.0f;
+    for (int u = 0; u < kUnroll; ++u) acc[u] = 0.0;
 
     for (int v0 = 0;;) {
 #pragma unroll
@@ -281,7 +281,7 @@ __device__ float backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_o
                     bool in_range;
                     float t = ste_terms((float)rx[u][e], p, in_range);
                     o[e] = in_range ? rg[u][e] : (T)0.0f;
-                    acc[u] = __builtin_fmaf((float)rg[u][e], t, acc[u]);
+                    acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t, acc[u]);
                 }
                 if (WRITE_GX) ov[v] = o;
             }
@@ -298,12 +298,12 @@ __device__ float backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_o
         }
     }
 
-    float sum = 0.0f;
+    double sum = 0.0;
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) sum += acc[u];
-    for (int i = tid; i < head; i += kBlock) sum += backward_elem<T, WRITE_GX>(x, gy, gx, i, p);
+    for (int i = tid; i < head; i += kBlock) sum = backward_elem<T, WRITE_GX>(x, gy, gx, i, p, sum);
     for (int i = head + nvec * N + tid; i < ck.n; i += kBlock)
-        sum += backward_elem<T, WRITE_GX>(x, gy, gx, i, p);
+        sum = backward_elem<T, WRITE_GX>(x, gy, gx, i, p, sum);
     return sum;
 }
 
@@ -318,7 +318,7 @@ __device__ void finalize_channel(const DevTensor &d, unsigned c, double *lds)
         unsigned k = j - o * d.cps;
         size_t idx = ((size_t)o * d.channels + c) * d.cps + k;
         // agent-scope load: the partial may have been written by a block on another XCD
-        acc += (double)__hip_atomic_load(&d.partial[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        acc += __hip_atomic_load(&d.partial[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = acc;
@@ -339,14 +339,14 @@ __device__ void finalize_channel(const DevTensor &d, unsigned c, double *lds)
 template <bool FUSED>
 __device__ void backward_block(const DevTensor &d, unsigned local_block)
 {
-    __shared__ float wave_part[kBlock / 64];
+    __shared__ double wave_part[kBlock / 64];
     __shared__ double fin_part[kBlock / 64];
     __shared__ unsigned is_last;
 
     const Chunk ck = locate_chunk(d, local_block);
     const bool write_gx = !(d.flags & 1u);
     Scale sc;
-    float sum;
+    double sum;
     if (d.dtype == 0)
         sum = write_gx ? backward_chunk<_Float16, true>(d, ck, sc) : backward_chunk<_Float16, false>(d, ck, sc);
     else
@@ -356,7 +356,7 @@ __device__ void backward_block(const DevTensor &d, unsigned local_block)
     if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = sum;
     __syncthreads();
     if (threadIdx.x == 0) {
-        float total = 0.0f;
+        double total = 0.0;
 #pragma unroll
         for (int w = 0; w < kBlock / 64; ++w) total += wave_part[w];
         __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
