@@ -119,6 +119,17 @@ __device__ __forceinline__ double wave_sum(double v)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Memory access helpers.  Pointers inside the descriptor are generic; naming the address space
+// gives global_load/global_store (not flat) for tensor data and scalar (SMEM) loads for values
+// that are uniform over the block and never written while a kernel runs (theta, the table).
+#define FQ_GLOBAL __attribute__((address_space(1)))
+#define FQ_CONST __attribute__((address_space(4)))
+
+template <typename U> __device__ __forceinline__ U ld_global(const U *p) { return *(const FQ_GLOBAL U *)p; }
+template <typename U> __device__ __forceinline__ void st_global(U *p, U v) { *(FQ_GLOBAL U *)p = v; }
+template <typename U> __device__ __forceinline__ U ld_uniform(const U *p) { return *(const FQ_CONST U *)p; }
+
+// ---------------------------------------------------------------------------------------------
 // Chunk addressing shared by forward and backward.
 struct Chunk {
     unsigned slab, channel;
@@ -152,13 +163,13 @@ template <typename T, bool EMIT_Q>
 __device__ __forceinline__ void forward_elem(const T *x, T *y, int8_t *q, int i, const QParams &p)
 {
     float qf;
-    float yf = fq_value((float)x[i], p, qf);
-    y[i] = (T)yf;
-    if (EMIT_Q && q) q[i] = code_of(qf);
+    float yf = fq_value((float)ld_global(x + i), p, qf);
+    st_global(y + i, (T)yf);
+    if (EMIT_Q && q) st_global(q + i, code_of(qf));
 }
 
 template <typename T, bool EMIT_Q>
-__device__ void forward_chunk(const DevTensor &d, unsigned local_block)
+__device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local_block)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
@@ -167,6 +178,7 @@ __device__ void forward_chunk(const DevTensor &d, unsigned local_block)
     T *y = (T *)d.y + ck.first;
     int8_t *q = (EMIT_Q && d.q) ? d.q + ck.first : nullptr;
     const int tid = threadIdx.x;
+    const float theta = ld_uniform(d.theta + ck.channel);
 
     const bool vector_ok = (((uintptr_t)x ^ (uintptr_t)y) & (kVecBytes - 1)) == 0;
     const int head = vector_ok ? head_elems<T>(x, ck.n) : ck.n;
@@ -174,19 +186,23 @@ __device__ void forward_chunk(const DevTensor &d, unsigned local_block)
     const VT *xv = (const VT *)(x + head);
     VT *yv = (VT *)(y + head);
 
-    // issue the first row of loads before the (long, binary64) scale evaluation
+    // Issue the first row of loads (straight-line: out-of-range lanes re-read the last vector)
+    // before the long binary64 scale evaluation, which then runs under the memory latency.
     VT r[kUnroll];
+    if (nvec > 0) {
+        const int last = nvec - 1;
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        int v = u * kBlock + tid;
-        if (v < nvec) r[u] = xv[v];
+        for (int u = 0; u < kUnroll; ++u) {
+            int v = u * kBlock + tid;
+            r[u] = ld_global(xv + (v < last ? v : last));
+        }
     }
 
-    const Scale sc = compute_scale(d.theta[ck.channel], d.eps, d.s_min, d.s_max);
+    const Scale sc = compute_scale(theta, d.eps, d.s_min, d.s_max);
     const QParams p = {sc.s, d.lo, d.hi};
-    if (d.s && ck.first == (long long)ck.channel * d.inner && tid == 0) d.s[ck.channel] = sc.s;
+    if (d.s && ck.first == (long long)ck.channel * d.inner && tid == 0) st_global(d.s + ck.channel, sc.s);
 
-    for (int v0 = 0;;) {
+    for (int v0 = 0; v0 < nvec;) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             int v = v0 + u * kBlock + tid;
@@ -195,19 +211,20 @@ __device__ void forward_chunk(const DevTensor &d, unsigned local_block)
                 float qf[N];
 #pragma unroll
                 for (int e = 0; e < N; ++e) o[e] = (T)fq_value((float)r[u][e], p, qf[e]);
-                yv[v] = o;
+                st_global(yv + v, o);
                 if (EMIT_Q && q) {
 #pragma unroll
-                    for (int e = 0; e < N; ++e) q[head + v * N + e] = code_of(qf[e]);
+                    for (int e = 0; e < N; ++e) st_global(q + head + v * N + e, code_of(qf[e]));
                 }
             }
         }
         v0 += kUnroll * kBlock;
         if (v0 >= nvec) break;
+        const int last = nvec - 1;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             int v = v0 + u * kBlock + tid;
-            if (v < nvec) r[u] = xv[v];
+            r[u] = ld_global(xv + (v < last ? v : last));
         }
     }
 
@@ -226,15 +243,15 @@ __device__ __forceinline__ double backward_elem(const T *x, const T *gy, T *gx, 
                                                 double acc)
 {
     bool in_range;
-    T g = gy[i];
-    float t = ste_terms((float)x[i], p, in_range);
-    if (WRITE_GX) gx[i] = in_range ? g : (T)0.0f;
+    T g = ld_global(gy + i);
+    float t = ste_terms((float)ld_global(x + i), p, in_range);
+    if (WRITE_GX) st_global(gx + i, in_range ? g : (T)0.0f);
     return __builtin_fma((double)(float)g, (double)t, acc);
 }
 
 // Per-thread sum of gy*t over this thread's elements of the chunk (binary64).
 template <typename T, bool WRITE_GX>
-__device__ double backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_out)
+__device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk &ck)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
@@ -242,6 +259,7 @@ __device__ double backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_
     const T *gy = (const T *)d.gy + ck.first;
     T *gx = WRITE_GX ? (T *)d.gx + ck.first : nullptr;
     const int tid = threadIdx.x;
+    const float theta = ld_uniform(d.theta + ck.channel);
 
     uintptr_t mis = (uintptr_t)x ^ (uintptr_t)gy;
     if (WRITE_GX) mis |= (uintptr_t)x ^ (uintptr_t)gx;
@@ -253,24 +271,25 @@ __device__ double backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_
     VT *ov = WRITE_GX ? (VT *)(gx + head) : nullptr;
 
     VT rx[kUnroll], rg[kUnroll];
+    if (nvec > 0) {
+        const int last = nvec - 1;
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        int v = u * kBlock + tid;
-        if (v < nvec) {
-            rx[u] = xv[v];
-            rg[u] = gv[v];
+        for (int u = 0; u < kUnroll; ++u) {
+            int v = u * kBlock + tid;
+            v = v < last ? v : last;
+            rx[u] = ld_global(xv + v);
+            rg[u] = ld_global(gv + v);
         }
     }
 
-    const Scale sc = compute_scale(d.theta[ck.channel], d.eps, d.s_min, d.s_max);
-    sc_out = sc;
+    const Scale sc = compute_scale(theta, d.eps, d.s_min, d.s_max);
     const QParams p = {sc.s, d.lo, d.hi};
 
     double acc[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) acc[u] = 0.0;
 
-    for (int v0 = 0;;) {
+    for (int v0 = 0; v0 < nvec;) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             int v = v0 + u * kBlock + tid;
@@ -283,18 +302,18 @@ __device__ double backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_
                     o[e] = in_range ? rg[u][e] : (T)0.0f;
                     acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t, acc[u]);
                 }
-                if (WRITE_GX) ov[v] = o;
+                if (WRITE_GX) st_global(ov + v, o);
             }
         }
         v0 += kUnroll * kBlock;
         if (v0 >= nvec) break;
+        const int last = nvec - 1;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             int v = v0 + u * kBlock + tid;
-            if (v < nvec) {
-                rx[u] = xv[v];
-                rg[u] = gv[v];
-            }
+            v = v < last ? v : last;
+            rx[u] = ld_global(xv + v);
+            rg[u] = ld_global(gv + v);
         }
     }
 
@@ -309,7 +328,9 @@ __device__ double backward_chunk(const DevTensor &d, const Chunk &ck, Scale &sc_
 
 // Sum the per-block partials of channel c in a fixed order (thread-strided binary64 sums, fixed
 // tree) and apply the chain rule through Eq. (3)-(4).  Block-wide; lds holds kBlock/64 doubles.
-__device__ void finalize_channel(const DevTensor &d, unsigned c, double *lds)
+// Partials are read with agent-scope loads: they may have been written by a block running on
+// another XCD, whose L2 is not this one.
+__device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c, double *lds)
 {
     const unsigned bpc = d.outer * d.cps;
     double acc = 0.0;
@@ -317,7 +338,6 @@ __device__ void finalize_channel(const DevTensor &d, unsigned c, double *lds)
         unsigned o = j / d.cps;
         unsigned k = j - o * d.cps;
         size_t idx = ((size_t)o * d.channels + c) * d.cps + k;
-        // agent-scope load: the partial may have been written by a block on another XCD
         acc += __hip_atomic_load(&d.partial[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     acc = wave_sum(acc);
@@ -327,17 +347,18 @@ __device__ void finalize_channel(const DevTensor &d, unsigned c, double *lds)
         double total = 0.0;
 #pragma unroll
         for (int w = 0; w < kBlock / 64; ++w) total += lds[w];
-        const float theta = d.theta[c];
+        const float theta = ld_uniform(d.theta + c);
         const Scale sc = compute_scale(theta, d.eps, d.s_min, d.s_max);
-        if (d.gs) d.gs[c] = (float)total;
-        if (d.gtheta) d.gtheta[c] = sc.clip_active ? 0.0f : (float)(total * sigmoid64((double)theta));
-        if (d.s) d.s[c] = sc.s;
+        if (d.gs) st_global(d.gs + c, (float)total);
+        if (d.gtheta) st_global(d.gtheta + c, sc.clip_active ? 0.0f : (float)(total * sigmoid64((double)theta)));
+        if (d.s) st_global(d.s + c, sc.s);
     }
     __syncthreads();
 }
 
-template <bool FUSED>
-__device__ void backward_block(const DevTensor &d, unsigned local_block)
+// One block of the backward grid.  T_RUNTIME: take the dtype from the descriptor.
+template <typename T, bool FUSED>
+__device__ __forceinline__ void backward_block(const DevTensor &d, unsigned local_block)
 {
     __shared__ double wave_part[kBlock / 64];
     __shared__ double fin_part[kBlock / 64];
@@ -345,12 +366,7 @@ __device__ void backward_block(const DevTensor &d, unsigned local_block)
 
     const Chunk ck = locate_chunk(d, local_block);
     const bool write_gx = !(d.flags & 1u);
-    Scale sc;
-    double sum;
-    if (d.dtype == 0)
-        sum = write_gx ? backward_chunk<_Float16, true>(d, ck, sc) : backward_chunk<_Float16, false>(d, ck, sc);
-    else
-        sum = write_gx ? backward_chunk<float, true>(d, ck, sc) : backward_chunk<float, false>(d, ck, sc);
+    double sum = write_gx ? backward_chunk<T, true>(d, ck) : backward_chunk<T, false>(d, ck);
 
     sum = wave_sum(sum);
     if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = sum;
@@ -359,12 +375,15 @@ __device__ void backward_block(const DevTensor &d, unsigned local_block)
         double total = 0.0;
 #pragma unroll
         for (int w = 0; w < kBlock / 64; ++w) total += wave_part[w];
+        // Agent-scope store: written through to where every XCD can see it.
         __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (FUSED) {
+            // Wait until that store has completed, then take a ticket.  Only the partial has to
+            // be published, so no cache write-back of the block's gx stores is requested (a full
+            // agent-scope release would flush the whole L2 once per block).
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             const unsigned bpc = d.outer * d.cps;
-            // release our partial, take a ticket; the block that draws the last ticket of this
-            // channel sees every other block's partial after its acquire
-            unsigned ticket = __hip_atomic_fetch_add(&d.counter[ck.channel], 1u, __ATOMIC_ACQ_REL,
+            unsigned ticket = __hip_atomic_fetch_add(&d.counter[ck.channel], 1u, __ATOMIC_RELAXED,
                                                      __HIP_MEMORY_SCOPE_AGENT);
             unsigned last = (ticket == bpc - 1u) ? 1u : 0u;
             if (last)   // leave the counter at zero for the next call
@@ -375,15 +394,17 @@ __device__ void backward_block(const DevTensor &d, unsigned local_block)
     if (FUSED) {
         __syncthreads();
         if (is_last) {
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            // every other block of this channel completed its partial store before its ticket
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
             finalize_channel(d, ck.channel, fin_part);
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Block -> tensor lookup for the multi-tensor grid: last tensor whose first block is <= block.
-__device__ __forceinline__ int find_by_block(const DevTensor *table, int n, unsigned block)
+// Multi-tensor grid: the table lives at the start of the workspace and is read through the scalar
+// cache.  Block -> tensor: last entry whose first block is <= block.
+__device__ __forceinline__ int find_by_block(const FQ_CONST DevTensor *table, int n, unsigned block)
 {
     int lo = 0, hi = n - 1;
     while (lo < hi) {
@@ -393,7 +414,7 @@ __device__ __forceinline__ int find_by_block(const DevTensor *table, int n, unsi
     return lo;
 }
 
-__device__ __forceinline__ int find_by_channel(const DevTensor *table, int n, unsigned chan)
+__device__ __forceinline__ int find_by_channel(const FQ_CONST DevTensor *table, int n, unsigned chan)
 {
     int lo = 0, hi = n - 1;
     while (lo < hi) {
@@ -403,21 +424,47 @@ __device__ __forceinline__ int find_by_channel(const DevTensor *table, int n, un
     return lo;
 }
 
-template <bool EMIT_Q>
-__global__ void __launch_bounds__(kBlock) forward_kernel(const KArgs a)
+// copy one table entry into registers, word by word through the scalar cache
+__device__ __forceinline__ DevTensor fetch(const DevTensor *table, int i)
 {
-    const DevTensor *dp = a.table ? &a.table[find_by_block(a.table, a.n, blockIdx.x)] : &a.one;
-    const DevTensor &d = *dp;
+    static_assert(sizeof(DevTensor) % 4 == 0, "descriptor is copied as 32-bit words");
+    DevTensor d;
+    const FQ_CONST unsigned *src = (const FQ_CONST unsigned *)(table + i);
+    unsigned *dst = (unsigned *)&d;
+#pragma unroll
+    for (unsigned w = 0; w < sizeof(DevTensor) / 4; ++w) dst[w] = src[w];
+    return d;
+}
+
+// Single tensor: descriptor in the kernel arguments (SGPRs), dtype fixed at compile time.
+template <typename T, bool EMIT_Q>
+__global__ void __launch_bounds__(kBlock) forward_kernel(const DevTensor d)
+{
+    forward_chunk<T, EMIT_Q>(d, blockIdx.x);
+}
+
+template <bool EMIT_Q>
+__global__ void __launch_bounds__(kBlock) forward_multi_kernel(const DevTensor *table, int n)
+{
+    const DevTensor d = fetch(table, find_by_block((const FQ_CONST DevTensor *)table, n, blockIdx.x));
     const unsigned local = blockIdx.x - d.block_begin;
     if (d.dtype == 0) forward_chunk<_Float16, EMIT_Q>(d, local);
     else forward_chunk<float, EMIT_Q>(d, local);
 }
 
-template <bool FUSED>
-__global__ void __launch_bounds__(kBlock) backward_kernel(const KArgs a)
+template <typename T, bool FUSED>
+__global__ void __launch_bounds__(kBlock) backward_kernel(const DevTensor d)
 {
-    const DevTensor *dp = a.table ? &a.table[find_by_block(a.table, a.n, blockIdx.x)] : &a.one;
-    backward_block<FUSED>(*dp, blockIdx.x - dp->block_begin);
+    backward_block<T, FUSED>(d, blockIdx.x);
+}
+
+template <bool FUSED>
+__global__ void __launch_bounds__(kBlock) backward_multi_kernel(const DevTensor *table, int n)
+{
+    const DevTensor d = fetch(table, find_by_block((const FQ_CONST DevTensor *)table, n, blockIdx.x));
+    const unsigned local = blockIdx.x - d.block_begin;
+    if (d.dtype == 0) backward_block<_Float16, FUSED>(d, local);
+    else backward_block<float, FUSED>(d, local);
 }
 
 // one block per channel: second pass of the two-pass backward, and the whole backward of tensors
@@ -425,8 +472,12 @@ __global__ void __launch_bounds__(kBlock) backward_kernel(const KArgs a)
 __global__ void __launch_bounds__(kBlock) finalize_kernel(const KArgs a)
 {
     __shared__ double fin_part[kBlock / 64];
-    const DevTensor *dp = a.table ? &a.table[find_by_channel(a.table, a.n, blockIdx.x)] : &a.one;
-    finalize_channel(*dp, blockIdx.x - dp->chan_begin, fin_part);
+    if (a.table) {
+        const DevTensor d = fetch(a.table, find_by_channel((const FQ_CONST DevTensor *)a.table, a.n, blockIdx.x));
+        finalize_channel(d, blockIdx.x - d.chan_begin, fin_part);
+    } else {
+        finalize_channel(a.one, blockIdx.x, fin_part);
+    }
 }
 
 // s[c] for every channel; used when a tensor has channels but no elements (forward)
@@ -434,7 +485,7 @@ __global__ void __launch_bounds__(kBlock) scale_kernel(const KArgs a, unsigned t
 {
     unsigned g = blockIdx.x * kBlock + threadIdx.x;
     if (g >= total_channels) return;
-    const DevTensor *dp = a.table ? &a.table[find_by_channel(a.table, a.n, g)] : &a.one;
+    const DevTensor *dp = a.table ? &a.table[find_by_channel((const FQ_CONST DevTensor *)a.table, a.n, g)] : &a.one;
     unsigned c = g - dp->chan_begin;
     if (dp->s) dp->s[c] = compute_scale(dp->theta[c], dp->eps, dp->s_min, dp->s_max).s;
 }
@@ -449,19 +500,43 @@ __global__ void __launch_bounds__(kBlock) fill_zero_kernel(unsigned *p, size_t w
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
+template <typename T> static void launch_forward_single(const DevTensor &d, unsigned blocks, bool emit_q, hipStream_t st)
+{
+    if (emit_q) hipLaunchKernelGGL((forward_kernel<T, true>), dim3(blocks), dim3(kBlock), 0, st, d);
+    else hipLaunchKernelGGL((forward_kernel<T, false>), dim3(blocks), dim3(kBlock), 0, st, d);
+}
+
+template <typename T> static void launch_backward_single(const DevTensor &d, unsigned blocks, bool fused, hipStream_t st)
+{
+    if (fused) hipLaunchKernelGGL((backward_kernel<T, true>), dim3(blocks), dim3(kBlock), 0, st, d);
+    else hipLaunchKernelGGL((backward_kernel<T, false>), dim3(blocks), dim3(kBlock), 0, st, d);
+}
+
 int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (emit_q) hipLaunchKernelGGL(forward_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, a);
-    else hipLaunchKernelGGL(forward_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, a);
+    if (a.table) {
+        if (emit_q) hipLaunchKernelGGL(forward_multi_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, a.table, a.n);
+        else hipLaunchKernelGGL(forward_multi_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, a.table, a.n);
+    } else if (a.one.dtype == 0) {
+        launch_forward_single<_Float16>(a.one, blocks, emit_q, st);
+    } else {
+        launch_forward_single<float>(a.one, blocks, emit_q, st);
+    }
     return (int)hipGetLastError();
 }
 
 int launch_backward(const KArgs &a, unsigned blocks, bool fused_finalize, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (fused_finalize) hipLaunchKernelGGL(backward_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, a);
-    else hipLaunchKernelGGL(backward_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, a);
+    if (a.table) {
+        if (fused_finalize) hipLaunchKernelGGL(backward_multi_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, a.table, a.n);
+        else hipLaunchKernelGGL(backward_multi_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, a.table, a.n);
+    } else if (a.one.dtype == 0) {
+        launch_backward_single<_Float16>(a.one, blocks, fused_finalize, st);
+    } else {
+        launch_backward_single<float>(a.one, blocks, fused_finalize, st);
+    }
     return (int)hipGetLastError();
 }
 
