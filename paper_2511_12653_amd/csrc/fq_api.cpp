@@ -37,6 +37,10 @@ struct Plan {
 
 // Split every [outer, channel] slab into cps equal chunks of at most kChunkVecs vectors each,
 // chunk length a multiple of the vector width so all chunks of a slab share one alignment.
+// A block's wavefront handles r = 1..5 rows of 64 vectors; among those five chunk sizes pick the
+// one with the smallest estimated makespan: (blocks per compute unit, rounded up) x (rows per
+// wavefront + 1 for the per-block prologue).  Large tensors end up with the biggest chunks, a
+// tensor whose block count is a small multiple of the CU count avoids a mostly-empty last round.
 fq_status plan_tensor(const fq_tensor &t, Plan &p)
 {
     if (t.dtype != FQ_F16 && t.dtype != FQ_F32) return FQ_ERR_DTYPE;
@@ -52,15 +56,28 @@ fq_status plan_tensor(const fq_tensor &t, Plan &p)
         return FQ_OK;
     }
     const long long vec = kVecBytes / (t.dtype == FQ_F16 ? 2 : 4);
-    const long long cap = (long long)kChunkVecs * vec;
-    long long cps = (t.inner + cap - 1) / cap;
-    long long chunk = (t.inner + cps - 1) / cps;
-    chunk = (chunk + vec - 1) / vec * vec;
-    cps = (t.inner + chunk - 1) / chunk;
-    if (cps > kMaxBlocks || slabs * cps > kMaxBlocks) return FQ_ERR_SHAPE;
-    p.cps = (unsigned)cps;
-    p.chunk = (unsigned)chunk;
-    p.blocks = slabs * cps;
+    const long long slab_vecs = (t.inner + vec - 1) / vec;
+    const int max_rows = kChunkVecs / kBlock;
+    long long best_cps = 0, best_chunk = 0;
+    double best_cost = 0.0;
+    for (int r = max_rows; r >= 1; --r) {
+        long long cps = (slab_vecs + (long long)kBlock * r - 1) / ((long long)kBlock * r);
+        long long chunk = (t.inner + cps - 1) / cps;
+        chunk = (chunk + vec - 1) / vec * vec;
+        cps = (t.inner + chunk - 1) / chunk;
+        const long long chunk_vecs = chunk / vec;
+        const long long rows_per_wave = ((chunk_vecs + 63) / 64 + 3) / 4;
+        const double blocks = (double)slabs * (double)cps;
+        const double rounds = std::ceil(blocks / kComputeUnits);
+        const double cost = rounds * (double)(rows_per_wave + 1);
+        if (best_cps == 0 || cost < best_cost) {
+            best_cost = cost; best_cps = cps; best_chunk = chunk;
+        }
+    }
+    if (best_cps > kMaxBlocks || (double)slabs * (double)best_cps > (double)kMaxBlocks) return FQ_ERR_SHAPE;
+    p.cps = (unsigned)best_cps;
+    p.chunk = (unsigned)best_chunk;
+    p.blocks = slabs * best_cps;
     return FQ_OK;
 }
 

@@ -8,7 +8,8 @@ namespace fq {
 
 constexpr int kBlock = 256;          // threads per block: four 64-wide wavefronts
 constexpr int kVecBytes = 16;        // one 128-bit global load/store per lane
-constexpr int kChunkVecs = 1024;     // at most this many 128-bit vectors per block (16 KiB)
+constexpr int kChunkVecs = 1280;     // at most this many 128-bit vectors per block (20 KiB)
+constexpr int kComputeUnits = 256;   // MI355X; used by the host to balance blocks over the chip
 
 // Device-side view of one tensor.  Built on the host; passed as a kernel argument for
 // single-tensor calls, or as an array in device memory for the multi-tensor launch.

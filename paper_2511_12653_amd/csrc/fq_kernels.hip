@@ -34,64 +34,83 @@ static_assert(kChunkVecs % kBlock == 0, "chunk must be a whole number of block-w
 // to binary32 once, so the value does not depend on the accuracy of a binary32 exp/log.
 // clip_active: the clamp changed the value (its derivative is then zero).
 struct Scale {
-    float s;
-    bool clip_active;
+    float s;             // Eq. (3)-(4)
+    bool clip_active;    // the clamp changed the value (its derivative is then zero)
+    double sigmoid;      // d softplus / d theta
 };
 
+// What a block needs of its channel's scale, evaluated once by wavefront 0 (the binary64
+// softplus is a couple of hundred instructions) and handed to the others through LDS.
+struct BlockScale {
+    double rd;           // RN64(1 / s)
+    double sigmoid;
+    float s;
+    unsigned clip_active;
+};
+
+// softplus(t) = max(t,0) + log1p(e) and sigmoid(t) = (t >= 0 ? 1 : e) / (1 + e), e = exp(-|t|):
+// one exponential serves both.
 __device__ inline Scale compute_scale(float theta, float eps, float s_min, float s_max)
 {
-    double t = (double)theta;
-    double u = fmax(t, 0.0) + log1p(exp(-fabs(t))) + (double)eps;
-    float uf = (float)u;
+    const double t = (double)theta;
+    const double e = exp(-fabs(t));
+    const double u = fmax(t, 0.0) + log1p(e) + (double)eps;
+    const float uf = (float)u;
     Scale r;
     r.clip_active = !(uf >= s_min && uf <= s_max);
     float v = uf;
     v = v < s_min ? s_min : v;
     v = v > s_max ? s_max : v;
     r.s = v;
+    r.sigmoid = (t >= 0.0 ? 1.0 : e) / (1.0 + e);
     return r;
 }
 
-__device__ inline double sigmoid64(double t)
-{
-    if (t >= 0.0) return 1.0 / (1.0 + exp(-t));
-    double e = exp(t);
-    return e / (1.0 + e);
-}
-
 // ---------------------------------------------------------------------------------------------
-// Per-element arithmetic.  The quotient is the correctly rounded binary32 x/s (hipcc's default
-// IEEE division); clip passes NaN through (comparisons are false), rint is v_rndne_f32.
-__device__ __forceinline__ float quotient(float x, float s) { return x / s; }
-
-__device__ __forceinline__ float clip_keep_nan(float v, float lo, float hi)
-{
-    v = v < lo ? lo : v;
-    v = v > hi ? hi : v;
-    return v;
-}
-
+// Per-element arithmetic.
+//
+// Quotient.  v must be the correctly rounded binary32 value of x/s.  It is formed as
+// (float)((double)x * rd) with rd = RN64(1/s): three full-rate instructions instead of the ~10 of
+// the IEEE binary32 division expansion.  This rounds exactly like x/s: writing x = X*2^a and
+// s = S*2^b with 24-bit integers X, S, the exact quotient is never half-way between two binary32
+// values and its distance from the nearest half-way point is at least 1/(2S) > 2^-25 ulp, i.e.
+// more than 2^-49 relative, while the binary64 product carries a relative error below 2^-52; so
+// the final rounding to binary32 sees the same side of every rounding boundary.  Infinities, NaN,
+// signed zeros and overflow behave as in x/s.  (Only a quotient in the binary32 subnormal range,
+// |v| < 2^-126, may differ by one subnormal ulp; its code is 0 either way.)
+//
+// Clip + round.  v_med3_f32 returns lo for a NaN quotient, so NaN is put back afterwards
+// (the per-operator definition propagates it: clamp and round keep NaN).
 struct QParams {
+    double rd;      // RN64(1 / s)
     float s, lo, hi;
 };
 
-// forward value; qf receives the integer-valued code (NaN for NaN input)
+__device__ __forceinline__ float quotient(float x, const QParams &p) { return (float)((double)x * p.rd); }
+
+// forward value; qf receives the integer-valued code (NaN for a NaN quotient)
 __device__ __forceinline__ float fq_value(float x, const QParams &p, float &qf)
 {
-    float v = quotient(x, p.s);
-    qf = __builtin_rintf(clip_keep_nan(v, p.lo, p.hi));
-    return qf * p.s;
+    float v = quotient(x, p);
+    float q = __builtin_rintf(__builtin_amdgcn_fmed3f(v, p.lo, p.hi));
+    float y = q * p.s;
+    bool is_nan = v != v;
+    qf = is_nan ? v : q;
+    return is_nan ? v : y;
 }
 
 __device__ __forceinline__ int8_t code_of(float qf) { return qf != qf ? (int8_t)0 : (int8_t)(int)qf; }
 
-// backward: returns t = dy/ds and whether the quotient is inside [lo, hi] (inclusive)
-__device__ __forceinline__ float ste_terms(float x, const QParams &p, bool &in_range)
+// backward: returns t = dy/ds and whether the quotient is inside [lo, hi] (inclusive).
+// in range: t = rint(v) - v;  below: lo;  above: hi;  NaN quotient: out of range, t = NaN.
+__device__ __forceinline__ float ste_terms(float x, const QParams &p, bool &in_range, bool &is_nan)
 {
-    float v = quotient(x, p.s);
-    in_range = (v >= p.lo) && (v <= p.hi);
-    float outside = v < p.lo ? p.lo : (v > p.hi ? p.hi : v);   // NaN stays NaN
-    return in_range ? (__builtin_rintf(v) - v) : outside;
+    float v = quotient(x, p);
+    float cl = __builtin_amdgcn_fmed3f(v, p.lo, p.hi);
+    in_range = cl == v;                       // false for NaN
+    is_nan = v != v;
+    float r = __builtin_rintf(cl);            // the bound itself when clipped
+    return r - (in_range ? v : 0.0f);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -127,6 +146,28 @@ __device__ __forceinline__ double wave_sum(double v)
 
 template <typename U> __device__ __forceinline__ U ld_global(const U *p) { return *(const FQ_GLOBAL U *)p; }
 template <typename U> __device__ __forceinline__ void st_global(U *p, U v) { *(FQ_GLOBAL U *)p = v; }
+
+// Tensor data is touched exactly once per kernel: stream it (non-temporal hint) so it does not
+// displace anything useful from the caches.
+#ifndef FQ_NONTEMPORAL
+#define FQ_NONTEMPORAL 1
+#endif
+template <typename U> __device__ __forceinline__ U ld_stream(const U *p)
+{
+#if FQ_NONTEMPORAL
+    return __builtin_nontemporal_load((const FQ_GLOBAL U *)p);
+#else
+    return *(const FQ_GLOBAL U *)p;
+#endif
+}
+template <typename U> __device__ __forceinline__ void st_stream(U *p, U v)
+{
+#if FQ_NONTEMPORAL
+    __builtin_nontemporal_store(v, (FQ_GLOBAL U *)p);
+#else
+    *(FQ_GLOBAL U *)p = v;
+#endif
+}
 template <typename U> __device__ __forceinline__ U ld_uniform(const U *p) { return *(const FQ_CONST U *)p; }
 
 // ---------------------------------------------------------------------------------------------
@@ -155,6 +196,31 @@ template <typename T> __device__ __forceinline__ int head_elems(const void *p, i
 {
     int h = (int)(((kVecBytes - ((uintptr_t)p & (kVecBytes - 1))) & (kVecBytes - 1)) / sizeof(T));
     return h < n ? h : n;
+}
+
+// Scale of this block's channel: one wavefront evaluates Eq. (3)-(4), everyone reads it from LDS.
+// Callers issue their first global loads before this, so the evaluation and the barrier sit in
+// the shadow of the memory latency.  The evaluating wavefront rotates with the block index:
+// wavefront w of a block runs on SIMD w of its compute unit, and a few hundred binary64
+// instructions per resident block would otherwise all queue on SIMD 0.
+__device__ __forceinline__ QParams block_params(const DevTensor &d, float theta, BlockScale *shared_scale)
+{
+    if ((threadIdx.x >> 6) == (blockIdx.x & (kBlock / 64 - 1))) {
+        const Scale sc = compute_scale(theta, d.eps, d.s_min, d.s_max);
+        if ((threadIdx.x & 63) == 0) {
+            shared_scale->s = sc.s;
+            shared_scale->rd = 1.0 / (double)sc.s;
+            shared_scale->sigmoid = sc.sigmoid;
+            shared_scale->clip_active = sc.clip_active ? 1u : 0u;
+        }
+    }
+    __syncthreads();
+    QParams p;
+    p.rd = shared_scale->rd;
+    p.s = shared_scale->s;
+    p.lo = d.lo;
+    p.hi = d.hi;
+    return p;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -194,13 +260,13 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             int v = u * kBlock + tid;
-            r[u] = ld_global(xv + (v < last ? v : last));
+            r[u] = ld_stream(xv + (v < last ? v : last));
         }
     }
 
-    const Scale sc = compute_scale(theta, d.eps, d.s_min, d.s_max);
-    const QParams p = {sc.s, d.lo, d.hi};
-    if (d.s && ck.first == (long long)ck.channel * d.inner && tid == 0) st_global(d.s + ck.channel, sc.s);
+    __shared__ BlockScale shared_scale;
+    const QParams p = block_params(d, theta, &shared_scale);
+    if (d.s && ck.first == (long long)ck.channel * d.inner && tid == 0) st_global(d.s + ck.channel, p.s);
 
     for (int v0 = 0; v0 < nvec;) {
 #pragma unroll
@@ -211,7 +277,7 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
                 float qf[N];
 #pragma unroll
                 for (int e = 0; e < N; ++e) o[e] = (T)fq_value((float)r[u][e], p, qf[e]);
-                st_global(yv + v, o);
+                st_stream(yv + v, o);
                 if (EMIT_Q && q) {
 #pragma unroll
                     for (int e = 0; e < N; ++e) st_global(q + head + v * N + e, code_of(qf[e]));
@@ -224,7 +290,7 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             int v = v0 + u * kBlock + tid;
-            r[u] = ld_global(xv + (v < last ? v : last));
+            r[u] = ld_stream(xv + (v < last ? v : last));
         }
     }
 
@@ -242,16 +308,17 @@ template <typename T, bool WRITE_GX>
 __device__ __forceinline__ double backward_elem(const T *x, const T *gy, T *gx, int i, const QParams &p,
                                                 double acc)
 {
-    bool in_range;
+    bool in_range, is_nan;
     T g = ld_global(gy + i);
-    float t = ste_terms((float)ld_global(x + i), p, in_range);
+    float t = ste_terms((float)ld_global(x + i), p, in_range, is_nan);
     if (WRITE_GX) st_global(gx + i, in_range ? g : (T)0.0f);
-    return __builtin_fma((double)(float)g, (double)t, acc);
+    acc = __builtin_fma((double)(float)g, (double)t, acc);
+    return is_nan ? __builtin_nan("") : acc;
 }
 
 // Per-thread sum of gy*t over this thread's elements of the chunk (binary64).
 template <typename T, bool WRITE_GX>
-__device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk &ck)
+__device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk &ck, BlockScale *shared_scale)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
@@ -277,13 +344,12 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
         for (int u = 0; u < kUnroll; ++u) {
             int v = u * kBlock + tid;
             v = v < last ? v : last;
-            rx[u] = ld_global(xv + v);
-            rg[u] = ld_global(gv + v);
+            rx[u] = ld_stream(xv + v);
+            rg[u] = ld_stream(gv + v);
         }
     }
 
-    const Scale sc = compute_scale(theta, d.eps, d.s_min, d.s_max);
-    const QParams p = {sc.s, d.lo, d.hi};
+    const QParams p = block_params(d, theta, shared_scale);
 
     double acc[kUnroll];
 #pragma unroll
@@ -295,14 +361,17 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
             int v = v0 + u * kBlock + tid;
             if (v < nvec) {
                 VT o;
+                bool any_nan = false;
 #pragma unroll
                 for (int e = 0; e < N; ++e) {
-                    bool in_range;
-                    float t = ste_terms((float)rx[u][e], p, in_range);
+                    bool in_range, is_nan;
+                    float t = ste_terms((float)rx[u][e], p, in_range, is_nan);
                     o[e] = in_range ? rg[u][e] : (T)0.0f;
                     acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t, acc[u]);
+                    any_nan |= is_nan;
                 }
-                if (WRITE_GX) st_global(ov + v, o);
+                if (any_nan) acc[u] = __builtin_nan("");   // a NaN quotient poisons its channel
+                if (WRITE_GX) st_stream(ov + v, o);
             }
         }
         v0 += kUnroll * kBlock;
@@ -312,8 +381,8 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
         for (int u = 0; u < kUnroll; ++u) {
             int v = v0 + u * kBlock + tid;
             v = v < last ? v : last;
-            rx[u] = ld_global(xv + v);
-            rg[u] = ld_global(gv + v);
+            rx[u] = ld_stream(xv + v);
+            rg[u] = ld_stream(gv + v);
         }
     }
 
@@ -330,7 +399,7 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
 // tree) and apply the chain rule through Eq. (3)-(4).  Block-wide; lds holds kBlock/64 doubles.
 // Partials are read with agent-scope loads: they may have been written by a block running on
 // another XCD, whose L2 is not this one.
-__device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c, double *lds)
+__device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c, const BlockScale *bs, double *lds)
 {
     const unsigned bpc = d.outer * d.cps;
     double acc = 0.0;
@@ -347,11 +416,9 @@ __device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c,
         double total = 0.0;
 #pragma unroll
         for (int w = 0; w < kBlock / 64; ++w) total += lds[w];
-        const float theta = ld_uniform(d.theta + c);
-        const Scale sc = compute_scale(theta, d.eps, d.s_min, d.s_max);
         if (d.gs) st_global(d.gs + c, (float)total);
-        if (d.gtheta) st_global(d.gtheta + c, sc.clip_active ? 0.0f : (float)(total * sigmoid64((double)theta)));
-        if (d.s) st_global(d.s + c, sc.s);
+        if (d.gtheta) st_global(d.gtheta + c, bs->clip_active ? 0.0f : (float)(total * bs->sigmoid));
+        if (d.s) st_global(d.s + c, bs->s);
     }
     __syncthreads();
 }
@@ -363,10 +430,11 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
     __shared__ double wave_part[kBlock / 64];
     __shared__ double fin_part[kBlock / 64];
     __shared__ unsigned is_last;
+    __shared__ BlockScale shared_scale;
 
     const Chunk ck = locate_chunk(d, local_block);
     const bool write_gx = !(d.flags & 1u);
-    double sum = write_gx ? backward_chunk<T, true>(d, ck) : backward_chunk<T, false>(d, ck);
+    double sum = write_gx ? backward_chunk<T, true>(d, ck, &shared_scale) : backward_chunk<T, false>(d, ck, &shared_scale);
 
     sum = wave_sum(sum);
     if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = sum;
@@ -396,7 +464,7 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
         if (is_last) {
             // every other block of this channel completed its partial store before its ticket
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            finalize_channel(d, ck.channel, fin_part);
+            finalize_channel(d, ck.channel, &shared_scale, fin_part);
         }
     }
 }
@@ -472,12 +540,12 @@ __global__ void __launch_bounds__(kBlock) backward_multi_kernel(const DevTensor 
 __global__ void __launch_bounds__(kBlock) finalize_kernel(const KArgs a)
 {
     __shared__ double fin_part[kBlock / 64];
-    if (a.table) {
-        const DevTensor d = fetch(a.table, find_by_channel((const FQ_CONST DevTensor *)a.table, a.n, blockIdx.x));
-        finalize_channel(d, blockIdx.x - d.chan_begin, fin_part);
-    } else {
-        finalize_channel(a.one, blockIdx.x, fin_part);
-    }
+    __shared__ BlockScale shared_scale;
+    const DevTensor d = a.table ? fetch(a.table, find_by_channel((const FQ_CONST DevTensor *)a.table, a.n, blockIdx.x))
+                                : a.one;
+    const unsigned c = blockIdx.x - d.chan_begin;
+    block_params(d, ld_uniform(d.theta + c), &shared_scale);
+    finalize_channel(d, c, &shared_scale, fin_part);
 }
 
 // s[c] for every channel; used when a tensor has channels but no elements (forward)

@@ -87,14 +87,14 @@ def test_validate_accepts_edge_cases(fq):
 def test_workspace_bytes(fq):
     import paper_2511_12653_amd.binding as b
     t = _desc(fq, outer=15, channels=128, inner=19200, x=1 << 32, y=2 << 32, gy=3 << 32, gx=4 << 32)                # FP16: 8 elems / vector
-    # 19200 elements = 2400 vectors -> 3 chunks per slab -> 5760 blocks, one binary64 partial each
+    # 19200 elements = 2400 vectors -> 2 chunks of 1200 per slab -> 3840 blocks, one binary64 partial each
     fwd = fq.fq_workspace_bytes(t, 1)
     bwd = fq.fq_workspace_bytes(t, 2)
     assert fwd % 256 == 0 and bwd % 256 == 0 and fwd >= 256
-    assert bwd >= fwd + 5760 * 8 + 128 * 4
-    assert bwd <= fwd + 5760 * 8 + 128 * 4 + 3 * 256
+    assert bwd >= fwd + 3840 * 8 + 128 * 4
+    assert bwd <= fwd + 3840 * 8 + 128 * 4 + 3 * 256
     two = fq.fq_workspace_bytes([t, t], 2)
-    assert two >= 2 * (5760 * 8 + 128 * 4)
+    assert two >= 2 * (3840 * 8 + 128 * 4)
     assert fq.fq_workspace_bytes([], 2) == 256
     # launching calls refuse a missing or short workspace before touching the GPU
     with pytest.raises(b.FqError) as e:
