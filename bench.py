@@ -9,9 +9,11 @@ the 256 MB Infinity Cache, so every step streams from HBM rather than from cache
 
 Prints one JSON line: whole-job GB/s (algorithmic bytes: forward 2b + backward 3b per element),
 the roofline position of the dominant kernel (the backward kernel, 3b bytes per element, timed
-with HIP events inside the timed region) and the CPU oracle timed on this host beside it.
+in every step of the timed region by HIP events that ride on the kernel's own dispatch) and the
+CPU oracle timed on this host beside it.
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -23,6 +25,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 RING_BYTES = 1200 << 20        # total footprint of the rotating buffer sets
+EVENT_EVERY = 8                # one bracketed step in this many
+# HBM bytes per backward launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counters (see profiles/);
+# None until counters have been taken for the current kernel.
+TRAFFIC_BYTES_PER_LAUNCH = None
 
 
 def main():
@@ -31,8 +37,12 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
+                    help="after the timed region also run N plain device copies of the 14745600-byte "
+                         "x tensor (torch copy_), so that a rocprofv3 --pmc run of this command holds a "
+                         "copy kernel of known size to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--no-kernel-events", action="store_true",
-                    help="do not bracket the backward kernel with events (roofline becomes null)")
+                    help="do not attach timing events to the backward kernel (roofline becomes null)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (got --gpus %d); "
@@ -69,27 +79,56 @@ def main():
                      device="cuda")
     stream = torch.cuda.current_stream()
 
-    def step(i, ev=None):
+    # Kernel timing inside the timed region, with raw HIP events on the launch stream.  A pair of
+    # event records costs the queue about as much as a small kernel, so (a) only every
+    # EVENT_EVERY-th step carries a pair, and (b) the backward kernel's duration is taken as a
+    # difference that cancels the pair's own overhead: steps of kind A bracket forward+backward,
+    # steps of kind B bracket the forward alone, and  t(backward) = mean(A) - mean(B).
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    sp = stream.cuda_stream
+
+    def new_event():
+        e = ctypes.c_void_p()
+        if hip.hipEventCreate(ctypes.byref(e)) != 0:
+            sys.exit("bench.py: hipEventCreate failed")
+        return e
+
+    def step(i, ev=None, kind=None):
         d = descs[i % ring]
+        if ev is not None:
+            hip.hipEventRecord(ev[0], sp)
         fq.fq_forward(d, stream)
-        if ev is not None:
-            ev[0].record(stream)
+        if kind == "fwd":
+            hip.hipEventRecord(ev[1], sp)
         fq.fq_backward(d, ws, stream)
-        if ev is not None:
-            ev[1].record(stream)
+        if kind == "fwd+bwd":
+            hip.hipEventRecord(ev[1], sp)
 
     for i in range(args.warmup):
         step(i)
-    events = None
+    events = {}
     if not args.no_kernel_events:
-        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                  for _ in range(args.steps)]
+        for n, i in enumerate(range(EVENT_EVERY - 1, args.steps, EVENT_EVERY)):
+            events[i] = ((new_event(), new_event()), "fwd+bwd" if n % 2 == 0 else "fwd")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, events[i] if events else None)
+        if i in events:
+            step(args.warmup + i, *events[i])
+        else:
+            step(args.warmup + i)
+    t_enq = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+
+    for i in range(args.copy_calibration):
+        x, _, y, _ = keep[i % ring]
+        y.copy_(x)
+    torch.cuda.synchronize()
 
     sec_per_step = (t1 - t0) / args.steps
     step_bytes = 5 * b * numel
@@ -97,14 +136,27 @@ def main():
 
     roofline = None
     if events:
-        dur = np.array([a.elapsed_time(z) for a, z in events]) * 1e-3     # seconds
-        bwd_bytes = 3 * b * numel
-        achieved = bwd_bytes / dur.mean() / 1e9
-        roofline = {"bound": "hbm", "kernel": "backward_kernel", "achieved": round(achieved, 1),
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": None, "bytes_per_launch": bwd_bytes,
-                    "avg_us": round(float(dur.mean()) * 1e6, 2),
-                    "min_us": round(float(dur.min()) * 1e6, 2)}
+        dur = {"fwd+bwd": [], "fwd": []}
+        for (a, z), kind in events.values():
+            ms = ctypes.c_float()
+            if hip.hipEventElapsedTime(ctypes.byref(ms), a, z) != 0:
+                sys.exit("bench.py: hipEventElapsedTime failed")
+            dur[kind].append(ms.value * 1e-3)
+            hip.hipEventDestroy(a)
+            hip.hipEventDestroy(z)
+        if dur["fwd"] and dur["fwd+bwd"]:
+            t_both, t_fwd = float(np.mean(dur["fwd+bwd"])), float(np.mean(dur["fwd"]))
+            t_bwd = t_both - t_fwd
+            bwd_bytes = 3 * b * numel
+            achieved = bwd_bytes / t_bwd / 1e9
+            roofline = {"bound": "hbm", "kernel": "backward_kernel<f16, fused>", "achieved": round(achieved, 1),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                        "traffic": TRAFFIC_BYTES_PER_LAUNCH, "bytes_per_launch": bwd_bytes,
+                        "avg_us": round(t_bwd * 1e6, 2),
+                        "method": "HIP events on the launch stream in the timed region: mean(bracket "
+                                  "fwd+bwd) - mean(bracket fwd); cancels the event pair's own cost",
+                        "bracket_fwd_bwd_us": round(t_both * 1e6, 2), "bracket_fwd_us": round(t_fwd * 1e6, 2),
+                        "samples": [len(dur["fwd+bwd"]), len(dur["fwd"])]}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -134,6 +186,7 @@ def main():
                    "io_dtype": "f16", "elements": numel, "bytes_per_step": step_bytes,
                    "ring_buffer_sets": int(ring), "ring_bytes": int(ring * set_bytes)},
         "elements_per_s": round(numel / sec_per_step, 1),
+        "host_enqueue_us_per_step": round((t_enq - t0) / args.steps * 1e6, 2),
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -568,28 +568,25 @@ __global__ void __launch_bounds__(kBlock) fill_zero_kernel(unsigned *p, size_t w
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
-template <typename T> static void launch_forward_single(const DevTensor &d, unsigned blocks, bool emit_q, hipStream_t st)
+// Launchers.
+template <typename K, typename... Args>
+static void launch(K kernel, unsigned blocks, hipStream_t st, Args... args)
 {
-    if (emit_q) hipLaunchKernelGGL((forward_kernel<T, true>), dim3(blocks), dim3(kBlock), 0, st, d);
-    else hipLaunchKernelGGL((forward_kernel<T, false>), dim3(blocks), dim3(kBlock), 0, st, d);
-}
-
-template <typename T> static void launch_backward_single(const DevTensor &d, unsigned blocks, bool fused, hipStream_t st)
-{
-    if (fused) hipLaunchKernelGGL((backward_kernel<T, true>), dim3(blocks), dim3(kBlock), 0, st, d);
-    else hipLaunchKernelGGL((backward_kernel<T, false>), dim3(blocks), dim3(kBlock), 0, st, d);
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kBlock), 0, st, args...);
 }
 
 int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     if (a.table) {
-        if (emit_q) hipLaunchKernelGGL(forward_multi_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, a.table, a.n);
-        else hipLaunchKernelGGL(forward_multi_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, a.table, a.n);
+        if (emit_q) launch(forward_multi_kernel<true>, blocks, st, a.table, a.n);
+        else launch(forward_multi_kernel<false>, blocks, st, a.table, a.n);
     } else if (a.one.dtype == 0) {
-        launch_forward_single<_Float16>(a.one, blocks, emit_q, st);
+        if (emit_q) launch(forward_kernel<_Float16, true>, blocks, st, a.one);
+        else launch(forward_kernel<_Float16, false>, blocks, st, a.one);
     } else {
-        launch_forward_single<float>(a.one, blocks, emit_q, st);
+        if (emit_q) launch(forward_kernel<float, true>, blocks, st, a.one);
+        else launch(forward_kernel<float, false>, blocks, st, a.one);
     }
     return (int)hipGetLastError();
 }
@@ -598,12 +595,14 @@ int launch_backward(const KArgs &a, unsigned blocks, bool fused_finalize, void *
 {
     hipStream_t st = (hipStream_t)stream;
     if (a.table) {
-        if (fused_finalize) hipLaunchKernelGGL(backward_multi_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, a.table, a.n);
-        else hipLaunchKernelGGL(backward_multi_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, a.table, a.n);
+        if (fused_finalize) launch(backward_multi_kernel<true>, blocks, st, a.table, a.n);
+        else launch(backward_multi_kernel<false>, blocks, st, a.table, a.n);
     } else if (a.one.dtype == 0) {
-        launch_backward_single<_Float16>(a.one, blocks, fused_finalize, st);
+        if (fused_finalize) launch(backward_kernel<_Float16, true>, blocks, st, a.one);
+        else launch(backward_kernel<_Float16, false>, blocks, st, a.one);
     } else {
-        launch_backward_single<float>(a.one, blocks, fused_finalize, st);
+        if (fused_finalize) launch(backward_kernel<float, true>, blocks, st, a.one);
+        else launch(backward_kernel<float, false>, blocks, st, a.one);
     }
     return (int)hipGetLastError();
 }
