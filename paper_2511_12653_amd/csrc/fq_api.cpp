@@ -142,7 +142,7 @@ fq_status make_layout(const fq_tensor *ts, int n, int mode, Layout &L)
     L.total = L.table_bytes;
     if (mode == FQ_MODE_BACKWARD) {
         L.counter_off = L.partial_off + round_up((size_t)L.partials * sizeof(double), kAlign);
-        L.total = L.counter_off + round_up((size_t)L.channels * sizeof(unsigned), kAlign);
+        L.total = L.counter_off + round_up((size_t)L.channels * sizeof(unsigned long long), kAlign);
     }
     if (L.total < kAlign) L.total = kAlign;
     return FQ_OK;
@@ -161,7 +161,7 @@ void build_table(const fq_tensor *ts, int n, const Layout &L, char *workspace, s
         d.x = t.x; d.y = t.y; d.q = t.q; d.theta = t.theta; d.s = t.s;
         d.gy = t.gy; d.gx = t.gx; d.gs = t.gs; d.gtheta = t.gtheta;
         d.partial = workspace ? (double *)(workspace + L.partial_off) + block : nullptr;
-        d.counter = workspace ? (unsigned *)(workspace + L.counter_off) + chan : nullptr;
+        d.slot = workspace ? (unsigned long long *)(workspace + L.counter_off) + chan : nullptr;
         d.inner = t.inner;
         d.slabs = p.slabs;
         d.channels = (unsigned)t.channels;

@@ -24,7 +24,7 @@ struct DevTensor {
     float *gs;
     float *gtheta;
     double *partial;           // [slabs * cps] per-block partial sums of gy*t (backward)
-    unsigned *counter;         // [channels] arrival tickets, zero between calls (backward)
+    unsigned long long *slot;  // [channels] exchange slot / arrival tickets, zero between calls (backward)
     long long inner;           // elements per slab
     unsigned slabs;            // outer * channels
     unsigned channels;

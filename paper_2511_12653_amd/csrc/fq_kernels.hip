@@ -395,10 +395,17 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
     return sum;
 }
 
+// Chain rule through Eq. (3)-(4) and the per-channel outputs of the backward pass.
+__device__ __forceinline__ void write_channel_grads(const DevTensor &d, unsigned c, double total, const BlockScale *bs)
+{
+    if (d.gs) st_global(d.gs + c, (float)total);
+    if (d.gtheta) st_global(d.gtheta + c, bs->clip_active ? 0.0f : (float)(total * bs->sigmoid));
+    if (d.s) st_global(d.s + c, bs->s);
+}
+
 // Sum the per-block partials of channel c in a fixed order (thread-strided binary64 sums, fixed
-// tree) and apply the chain rule through Eq. (3)-(4).  Block-wide; lds holds kBlock/64 doubles.
-// Partials are read with agent-scope loads: they may have been written by a block running on
-// another XCD, whose L2 is not this one.
+// tree).  Block-wide; lds holds kBlock/64 doubles.  Partials are read with agent-scope loads:
+// they may have been written by a block running on another XCD, whose L2 is not this one.
 __device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c, const BlockScale *bs, double *lds)
 {
     const unsigned bpc = d.outer * d.cps;
@@ -416,14 +423,24 @@ __device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c,
         double total = 0.0;
 #pragma unroll
         for (int w = 0; w < kBlock / 64; ++w) total += lds[w];
-        if (d.gs) st_global(d.gs + c, (float)total);
-        if (d.gtheta) st_global(d.gtheta + c, bs->clip_active ? 0.0f : (float)(total * bs->sigmoid));
-        if (d.s) st_global(d.s + c, bs->s);
+        write_channel_grads(d, c, total, bs);
     }
     __syncthreads();
 }
 
-// One block of the backward grid.  T_RUNTIME: take the dtype from the descriptor.
+// One block of the backward grid.
+//
+// How the blocks of a channel combine their sums (FUSED; no float atomics, fixed order):
+//   1 block per channel   the block writes the channel's gradients itself;
+//   2 blocks per channel  each swaps its sum into the channel's 64-bit slot; the one that finds
+//                         its partner's sum there adds the two (a+b = b+a) and clears the slot:
+//                         one atomic round trip, the payload travels in the atomic itself;
+//   more                  each block stores its sum, waits for that store, then draws a ticket
+//                         from the slot; the block with the last ticket re-reads all sums in index
+//                         order and clears the slot.
+// The slot is zero between calls.  (A sum of +0.0 is swapped in as -0.0 so that it differs from
+// an empty slot; it adds the same.)
+// Without FUSED the sums are only stored and finalize_kernel adds them in a second launch.
 template <typename T, bool FUSED>
 __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned local_block)
 {
@@ -439,27 +456,41 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
     sum = wave_sum(sum);
     if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = sum;
     __syncthreads();
+    const unsigned bpc = d.outer * d.cps;
     if (threadIdx.x == 0) {
         double total = 0.0;
 #pragma unroll
         for (int w = 0; w < kBlock / 64; ++w) total += wave_part[w];
-        // Agent-scope store: written through to where every XCD can see it.
-        __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (FUSED) {
-            // Wait until that store has completed, then take a ticket.  Only the partial has to
-            // be published, so no cache write-back of the block's gx stores is requested (a full
-            // agent-scope release would flush the whole L2 once per block).
+        unsigned last = 0u;
+        if (!FUSED) {
+            __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else if (bpc == 1u) {
+            write_channel_grads(d, ck.channel, total, &shared_scale);
+        } else if (bpc == 2u) {
+            unsigned long long mine = __builtin_bit_cast(unsigned long long, total);
+            if (mine == 0ull) mine = 0x8000000000000000ull;
+            const unsigned long long theirs = __hip_atomic_exchange(&d.slot[ck.channel], mine, __ATOMIC_RELAXED,
+                                                                    __HIP_MEMORY_SCOPE_AGENT);
+            if (theirs != 0ull) {
+                __hip_atomic_store(&d.slot[ck.channel], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const double both = (__builtin_bit_cast(double, theirs) + total) + 0.0;
+                write_channel_grads(d, ck.channel, both, &shared_scale);
+            }
+        } else {
+            // Agent-scope store: written through to where every XCD can see it.  Wait until it
+            // has completed, then take a ticket.  Only the partial has to be published, so no
+            // cache write-back of the block's gx stores is requested (a full agent-scope release
+            // would flush the whole L2 once per block).
+            __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            const unsigned bpc = d.outer * d.cps;
-            unsigned ticket = __hip_atomic_fetch_add(&d.counter[ck.channel], 1u, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-            unsigned last = (ticket == bpc - 1u) ? 1u : 0u;
-            if (last)   // leave the counter at zero for the next call
-                __hip_atomic_store(&d.counter[ck.channel], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            is_last = last;
+            const unsigned long long ticket = __hip_atomic_fetch_add(&d.slot[ck.channel], 1ull, __ATOMIC_RELAXED,
+                                                                     __HIP_MEMORY_SCOPE_AGENT);
+            last = (ticket == (unsigned long long)(bpc - 1u)) ? 1u : 0u;
+            if (last) __hip_atomic_store(&d.slot[ck.channel], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+        is_last = last;
     }
-    if (FUSED) {
+    if (FUSED && bpc > 2u) {
         __syncthreads();
         if (is_last) {
             // every other block of this channel completed its partial store before its ticket

@@ -91,10 +91,10 @@ def test_workspace_bytes(fq):
     fwd = fq.fq_workspace_bytes(t, 1)
     bwd = fq.fq_workspace_bytes(t, 2)
     assert fwd % 256 == 0 and bwd % 256 == 0 and fwd >= 256
-    assert bwd >= fwd + 3840 * 8 + 128 * 4
-    assert bwd <= fwd + 3840 * 8 + 128 * 4 + 3 * 256
+    assert bwd >= fwd + 3840 * 8 + 128 * 8
+    assert bwd <= fwd + 3840 * 8 + 128 * 8 + 3 * 256
     two = fq.fq_workspace_bytes([t, t], 2)
-    assert two >= 2 * (3840 * 8 + 128 * 4)
+    assert two >= 2 * (3840 * 8 + 128 * 8)
     assert fq.fq_workspace_bytes([], 2) == 256
     # launching calls refuse a missing or short workspace before touching the GPU
     with pytest.raises(b.FqError) as e:
