@@ -48,13 +48,69 @@ struct BlockScale {
     unsigned clip_active;
 };
 
+// exp(-a) for a >= 0 in binary64, a few ulp: a = n ln2 + r with |r| <= ln2/2 (two-constant
+// reduction, n ln2_hi is exact), exp(-r) by its Taylor polynomial of degree 13 (remainder below
+// 2^-57), scaled by 2^-n.  Short on purpose: it sits in every block's prologue.
+__device__ __forceinline__ double exp_neg(double a)
+{
+    if (!(a < 746.0)) return a != a ? a : 0.0;                   // underflows to 0; NaN stays NaN
+    const double n = __builtin_rint(a * 1.4426950408889634074);      // a / ln2
+    double r = __builtin_fma(-n, 6.93147180369123816490e-01, a);     // ln2_hi, 21 trailing zero bits
+    r = __builtin_fma(-n, 1.90821492927058770002e-10, r);            // ln2_lo
+    const double x = -r;
+    double p = 1.0 / 6227020800.0;                                     // 1/13!
+    p = __builtin_fma(p, x, 1.0 / 479001600.0);
+    p = __builtin_fma(p, x, 1.0 / 39916800.0);
+    p = __builtin_fma(p, x, 1.0 / 3628800.0);
+    p = __builtin_fma(p, x, 1.0 / 362880.0);
+    p = __builtin_fma(p, x, 1.0 / 40320.0);
+    p = __builtin_fma(p, x, 1.0 / 5040.0);
+    p = __builtin_fma(p, x, 1.0 / 720.0);
+    p = __builtin_fma(p, x, 1.0 / 120.0);
+    p = __builtin_fma(p, x, 1.0 / 24.0);
+    p = __builtin_fma(p, x, 1.0 / 6.0);
+    p = __builtin_fma(p, x, 0.5);
+    p = __builtin_fma(p, x, 1.0);
+    p = __builtin_fma(p, x, 1.0);
+    return __builtin_ldexp(p, -(int)n);
+}
+
+// log(1 + e) for 0 <= e <= 1 in binary64, a few ulp: 2 atanh(z) with z = e / (2 + e) <= 1/3,
+// odd series up to z^35 (next term below 2^-58 of the sum).  No cancellation for small e.
+__device__ __forceinline__ double log1p_unit(double e)
+{
+    const double z = e / (2.0 + e);
+    const double w = z * z;
+    double p = 1.0 / 35.0;
+    p = __builtin_fma(p, w, 1.0 / 33.0);
+    p = __builtin_fma(p, w, 1.0 / 31.0);
+    p = __builtin_fma(p, w, 1.0 / 29.0);
+    p = __builtin_fma(p, w, 1.0 / 27.0);
+    p = __builtin_fma(p, w, 1.0 / 25.0);
+    p = __builtin_fma(p, w, 1.0 / 23.0);
+    p = __builtin_fma(p, w, 1.0 / 21.0);
+    p = __builtin_fma(p, w, 1.0 / 19.0);
+    p = __builtin_fma(p, w, 1.0 / 17.0);
+    p = __builtin_fma(p, w, 1.0 / 15.0);
+    p = __builtin_fma(p, w, 1.0 / 13.0);
+    p = __builtin_fma(p, w, 1.0 / 11.0);
+    p = __builtin_fma(p, w, 1.0 / 9.0);
+    p = __builtin_fma(p, w, 1.0 / 7.0);
+    p = __builtin_fma(p, w, 1.0 / 5.0);
+    p = __builtin_fma(p, w, 1.0 / 3.0);
+    p = __builtin_fma(p, w, 1.0);
+    return 2.0 * z * p;
+}
+
 // softplus(t) = max(t,0) + log1p(e) and sigmoid(t) = (t >= 0 ? 1 : e) / (1 + e), e = exp(-|t|):
-// one exponential serves both.
-__device__ inline Scale compute_scale(float theta, float eps, float s_min, float s_max)
+// one exponential serves both.  The binary64 value is rounded to binary32 once; a few ulp of
+// binary64 error move that rounding with probability ~1e-8 per channel.
+template <bool NEED_SIGMOID>
+__device__ __forceinline__ Scale compute_scale(float theta, float eps, float s_min, float s_max)
 {
     const double t = (double)theta;
-    const double e = exp(-fabs(t));
-    const double u = fmax(t, 0.0) + log1p(e) + (double)eps;
+    const double e = exp_neg(__builtin_fabs(t));
+    const double u = __builtin_fmax(t, 0.0) + log1p_unit(e) + (double)eps;
     const float uf = (float)u;
     Scale r;
     r.clip_active = !(uf >= s_min && uf <= s_max);
@@ -62,7 +118,7 @@ __device__ inline Scale compute_scale(float theta, float eps, float s_min, float
     v = v < s_min ? s_min : v;
     v = v > s_max ? s_max : v;
     r.s = v;
-    r.sigmoid = (t >= 0.0 ? 1.0 : e) / (1.0 + e);
+    r.sigmoid = NEED_SIGMOID ? (t >= 0.0 ? 1.0 : e) / (1.0 + e) : 0.0;
     return r;
 }
 
@@ -203,10 +259,11 @@ template <typename T> __device__ __forceinline__ int head_elems(const void *p, i
 // the shadow of the memory latency.  The evaluating wavefront rotates with the block index:
 // wavefront w of a block runs on SIMD w of its compute unit, and a few hundred binary64
 // instructions per resident block would otherwise all queue on SIMD 0.
+template <bool NEED_SIGMOID>
 __device__ __forceinline__ QParams block_params(const DevTensor &d, float theta, BlockScale *shared_scale)
 {
     if ((threadIdx.x >> 6) == (blockIdx.x & (kBlock / 64 - 1))) {
-        const Scale sc = compute_scale(theta, d.eps, d.s_min, d.s_max);
+        const Scale sc = compute_scale<NEED_SIGMOID>(theta, d.eps, d.s_min, d.s_max);
         if ((threadIdx.x & 63) == 0) {
             shared_scale->s = sc.s;
             shared_scale->rd = 1.0 / (double)sc.s;
@@ -265,7 +322,7 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
     }
 
     __shared__ BlockScale shared_scale;
-    const QParams p = block_params(d, theta, &shared_scale);
+    const QParams p = block_params<false>(d, theta, &shared_scale);
     if (d.s && ck.first == (long long)ck.channel * d.inner && tid == 0) st_global(d.s + ck.channel, p.s);
 
     for (int v0 = 0; v0 < nvec;) {
@@ -349,7 +406,7 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
         }
     }
 
-    const QParams p = block_params(d, theta, shared_scale);
+    const QParams p = block_params<true>(d, theta, shared_scale);
 
     double acc[kUnroll];
 #pragma unroll
@@ -575,7 +632,7 @@ __global__ void __launch_bounds__(kBlock) finalize_kernel(const KArgs a)
     const DevTensor d = a.table ? fetch(a.table, find_by_channel((const FQ_CONST DevTensor *)a.table, a.n, blockIdx.x))
                                 : a.one;
     const unsigned c = blockIdx.x - d.chan_begin;
-    block_params(d, ld_uniform(d.theta + c), &shared_scale);
+    block_params<true>(d, ld_uniform(d.theta + c), &shared_scale);
     finalize_channel(d, c, &shared_scale, fin_part);
 }
 
@@ -586,7 +643,7 @@ __global__ void __launch_bounds__(kBlock) scale_kernel(const KArgs a, unsigned t
     if (g >= total_channels) return;
     const DevTensor *dp = a.table ? &a.table[find_by_channel((const FQ_CONST DevTensor *)a.table, a.n, g)] : &a.one;
     unsigned c = g - dp->chan_begin;
-    if (dp->s) dp->s[c] = compute_scale(dp->theta[c], dp->eps, dp->s_min, dp->s_max).s;
+    if (dp->s) dp->s[c] = compute_scale<false>(dp->theta[c], dp->eps, dp->s_min, dp->s_max).s;
 }
 
 __global__ void __launch_bounds__(kBlock) fill_zero_kernel(unsigned *p, size_t words)

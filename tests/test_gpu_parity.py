@@ -169,6 +169,31 @@ def test_scale_clamp_and_eps():
     _fwd_bwd(case, "scale_clamp_eps")
 
 
+def test_scale_sweep_bit_exact():
+    """Eq. (3)-(4) over two million theta values (dense sweep, random, specials), through the
+    scale-only path of a tensor with channels but no elements."""
+    from oracle import fq_oracle
+    rng = np.random.default_rng(2511)
+    theta = np.concatenate([
+        np.linspace(-120.0, 100.0, 1 << 20), rng.standard_normal(1 << 19) * 4.0,
+        rng.uniform(-20.0, 20.0, 1 << 19),
+        [0.0, -0.0, 0.5, 20.0, -20.0, 88.7, -87.3, -103.9, -104.0, -745.0, -800.0, 745.0, 1e30, -1e30,
+         3.4e38, -3.4e38, np.inf, -np.inf, 1e-30, -1e-30, 1e-45]]).astype(np.float32)
+    for eps, s_min, s_max in [(0.0, fq.FLT_MIN, float("inf")), (1e-4, 2.0 ** -14, 512.0)]:
+        H.say("scale sweep: %d thetas eps=%g s_min=%g s_max=%g" % (theta.size, eps, s_min, s_max))
+        th = H.dev(theta)
+        s = torch.full((theta.size,), float("nan"), device="cuda")
+        d = fq.FqTensor.from_torch(0, theta.size, 8, -128, 127, theta=th, s=s, dtype=fq.FQ_F16,
+                                   eps=eps, s_min=s_min, s_max=s_max)
+        fq.fq_forward(d)
+        torch.cuda.synchronize()
+        ref, _ = fq_oracle.scale(theta, eps, s_min, s_max)
+        got = s.cpu().numpy()
+        bad = np.nonzero(got.view(np.uint32) != ref.view(np.uint32))[0]
+        assert bad.size == 0, "scale differs for theta=%r: %r vs %r" % (
+            theta[bad[:5]], got[bad[:5]], ref[bad[:5]])
+
+
 def test_non_finite_inputs():
     x = np.array([np.inf, -np.inf, np.nan, 1.0, -0.0, 0.0, 1e-40, 65504.0] * 40, np.float32)
     gy = np.array([1.0, np.nan, 2.0, 3.0, np.inf, 4.0, 5.0, 6.0] * 40, np.float32)
