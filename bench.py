@@ -26,9 +26,22 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 RING_BYTES = 1200 << 20        # total footprint of the rotating buffer sets
 EVENT_EVERY = 8                # one bracketed step in this many
-# HBM bytes per backward launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counters (see profiles/);
-# None until counters have been taken for the current kernel.
-TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM bytes per backward launch on the headline tensor, from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+# counter runs summarised in profiles/ (each scaled by a plain copy of known size in the same run).
+# Set to None whenever the backward kernel changes until the counters are taken again.
+TRAFFIC_BYTES_PER_LAUNCH = 44445594
+
+WORKLOAD_TEXT = {
+    "act_fp32_per_tensor": "act_fp32_per_tensor: FP32 1x128x30x40, one scale, codes -128..127, forward + STE backward",
+    "feature_fp16_per_channel": "feature_fp16_per_channel: FP16 1x384x120x160 NCHW, 384 per-channel scales, "
+                                "codes -128..127, forward + STE backward",
+    "conv_weights_fp32": "conv_weights_fp32: FP32 384x384x3x3 + 128x128x3x3, per-output-channel scales, codes "
+                         "-127..127, forward + STE backward, one multi-tensor launch per pass",
+    "train_batch_fp16": "train_batch_fp16: FP16 15x128x120x160, 128 per-channel scales, codes -128..127, "
+                        "forward + STE backward",
+    "multi_tensor_mixed": "multi_tensor_mixed: 64 mixed FP16/FP32, 4/8-bit, per-tensor/per-channel tensors, "
+                          "about 1 GiB of inputs, forward + STE backward, one multi-tensor launch per pass",
+}
 
 
 def main():
@@ -36,6 +49,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="feature_fp16_per_channel",
+                    help="one of paper_2511_12653_amd.workloads.WORKLOAD_NAMES (default: the headline "
+                         "tensor); lists of tensors go through fq_multi_tensor, one launch per pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="after the timed region also run N plain device copies of the 14745600-byte "
@@ -57,27 +73,46 @@ def main():
         sys.exit("bench.py: no GPU visible; there is no CPU fallback")
     torch.cuda.set_device(0)
 
-    case = workloads.make("feature_fp16_per_channel")[0]
-    numel, b = case.numel, case.itemsize
-    set_bytes = 4 * numel * b
-    ring = max(2, RING_BYTES // set_bytes)
+    if args.workload not in workloads.WORKLOAD_NAMES:
+        sys.exit("bench.py: unknown workload %r (choose from %s)" % (args.workload, ", ".join(workloads.WORKLOAD_NAMES)))
+    cases = workloads.make(args.workload)
+    multi = len(cases) > 1
+    numel = sum(cs.numel for cs in cases)
+    io_bytes = sum(cs.numel * cs.itemsize for cs in cases)        # sum over tensors of b * elements
+    set_bytes = 4 * io_bytes
+    ring = max(2, RING_BYTES // set_bytes) if set_bytes < RING_BYTES else 1
 
-    hx = torch.from_numpy(case.x.reshape(-1))
-    hg = torch.from_numpy(case.gy.reshape(-1))
-    theta = torch.from_numpy(case.theta).cuda()
-    c = case.channels
-    gs = torch.empty(c, device="cuda")
-    gtheta = torch.empty(c, device="cuda")
+    host = [(torch.from_numpy(cs.x.reshape(-1)), torch.from_numpy(cs.gy.reshape(-1)),
+             torch.from_numpy(cs.theta).cuda(), torch.empty(cs.channels, device="cuda"),
+             torch.empty(cs.channels, device="cuda")) for cs in cases]
     descs, keep = [], []
     for _ in range(ring):
-        x, gy = hx.cuda(), hg.cuda()
-        y, gx = torch.empty_like(x), torch.empty_like(x)
-        keep.append((x, gy, y, gx))
-        descs.append(fq.FqTensor.from_torch(case.outer, c, case.inner, case.qmin, case.qmax,
-                                            x=x, y=y, theta=theta, gy=gy, gx=gx, gs=gs, gtheta=gtheta))
+        group = []
+        for cs, (hx, hg, theta, gs, gtheta) in zip(cases, host):
+            x, gy = hx.cuda(), hg.cuda()
+            y, gx = torch.empty_like(x), torch.empty_like(x)
+            keep.append((x, gy, y, gx))
+            group.append(fq.FqTensor.from_torch(cs.outer, cs.channels, cs.inner, cs.qmin, cs.qmax, x=x, y=y,
+                                                theta=theta, gy=gy, gx=gx, gs=gs, gtheta=gtheta,
+                                                eps=cs.eps, s_min=cs.s_min, s_max=cs.s_max, flags=cs.flags))
+        descs.append(fq.fq_tensor_array(group) if multi else group[0])
     ws = torch.zeros(fq.fq_workspace_bytes(descs[0], fq.FQ_MODE_BACKWARD) // 4, dtype=torch.int32,
                      device="cuda")
     stream = torch.cuda.current_stream()
+    case, c, b = cases[0], cases[0].channels, cases[0].itemsize
+
+    if multi:
+        def run_forward(d):
+            fq.fq_multi_tensor(d, fq.FQ_MODE_FORWARD, ws, stream)
+
+        def run_backward(d):
+            fq.fq_multi_tensor(d, fq.FQ_MODE_BACKWARD, ws, stream)
+    else:
+        def run_forward(d):
+            fq.fq_forward(d, stream)
+
+        def run_backward(d):
+            fq.fq_backward(d, ws, stream)
 
     # Kernel timing inside the timed region, with raw HIP events on the launch stream.  A pair of
     # event records costs the queue about as much as a small kernel, so (a) only every
@@ -101,10 +136,10 @@ def main():
         d = descs[i % ring]
         if ev is not None:
             hip.hipEventRecord(ev[0], sp)
-        fq.fq_forward(d, stream)
+        run_forward(d)
         if kind == "fwd":
             hip.hipEventRecord(ev[1], sp)
-        fq.fq_backward(d, ws, stream)
+        run_backward(d)
         if kind == "fwd+bwd":
             hip.hipEventRecord(ev[1], sp)
 
@@ -126,12 +161,12 @@ def main():
     t1 = time.perf_counter()
 
     for i in range(args.copy_calibration):
-        x, _, y, _ = keep[i % ring]
+        x, _, y, _ = keep[i % len(keep)]
         y.copy_(x)
     torch.cuda.synchronize()
 
     sec_per_step = (t1 - t0) / args.steps
-    step_bytes = 5 * b * numel
+    step_bytes = 5 * io_bytes
     value = step_bytes / sec_per_step / 1e9
 
     roofline = None
@@ -147,11 +182,14 @@ def main():
         if dur["fwd"] and dur["fwd+bwd"]:
             t_both, t_fwd = float(np.mean(dur["fwd+bwd"])), float(np.mean(dur["fwd"]))
             t_bwd = t_both - t_fwd
-            bwd_bytes = 3 * b * numel
+            bwd_bytes = 3 * io_bytes
             achieved = bwd_bytes / t_bwd / 1e9
-            roofline = {"bound": "hbm", "kernel": "backward_kernel<f16, fused>", "achieved": round(achieved, 1),
+            kname = "backward_multi_kernel<fused>" if multi else "backward_kernel<%s, fused>" % (
+                "f16" if b == 2 else "f32")
+            roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                        "traffic": TRAFFIC_BYTES_PER_LAUNCH, "bytes_per_launch": bwd_bytes,
+                        "traffic": TRAFFIC_BYTES_PER_LAUNCH if args.workload == "feature_fp16_per_channel" else None,
+                        "bytes_per_launch": bwd_bytes,
                         "avg_us": round(t_bwd * 1e6, 2),
                         "method": "HIP events on the launch stream in the timed region: mean(bracket "
                                   "fwd+bwd) - mean(bracket fwd); cancels the event pair's own cost",
@@ -162,28 +200,36 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import fq_oracle
         fq_oracle.lib()
+        # bounded sample: whole tensors of the workload, in order, until about 40 M elements
+        sample, n_sample = [], 0
+        for cs in cases:
+            if sample and n_sample + cs.numel > 40_000_000:
+                break
+            sample.append(cs)
+            n_sample += cs.numel
+        sample_bytes = 5 * sum(cs.numel * cs.itemsize for cs in sample)
         reps, times = 3, []
         for _ in range(reps):
             c0 = time.perf_counter()
-            s, active = fq_oracle.scale(case.theta)
-            fq_oracle.forward(case.x, s, case.qmin, case.qmax, case.outer, c, case.inner, want_q=False)
-            fq_oracle.backward(case.x, case.gy, s, case.theta, active, case.qmin, case.qmax,
-                               case.outer, c, case.inner)
+            for cs in sample:
+                s_, active = fq_oracle.scale(cs.theta, cs.eps, cs.s_min, cs.s_max)
+                fq_oracle.forward(cs.x, s_, cs.qmin, cs.qmax, cs.outer, cs.channels, cs.inner, want_q=False)
+                fq_oracle.backward(cs.x, cs.gy, s_, cs.theta, active, cs.qmin, cs.qmax,
+                                   cs.outer, cs.channels, cs.inner)
             times.append(time.perf_counter() - c0)
         med = sorted(times)[len(times) // 2]
-        cpu = {"value": round(step_bytes / med / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-               "sample": "the whole workload tensor (7372800 elements, fwd+bwd), median of %d runs, "
-                         "%.2f s each" % (reps, med),
-               "elements_per_s": round(numel / med, 1)}
+        cpu = {"value": round(sample_bytes / med / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "%d of %d tensors of the workload (%d elements, fwd+bwd), median of %d runs, "
+                         "%.2f s each" % (len(sample), len(cases), n_sample, reps, med),
+               "elements_per_s": round(n_sample / med, 1)}
 
     out = {
         "metric": "fake-quant fwd+bwd GB/s", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "feature_fp16_per_channel: FP16 1x384x120x160 NCHW, 384 per-channel "
-                               "scales, codes -128..127, forward + STE backward",
-                   "io_dtype": "f16", "elements": numel, "bytes_per_step": step_bytes,
+        "config": {"workload": WORKLOAD_TEXT[args.workload], "tensors": len(cases),
+                   "launches_per_step": 2, "elements": numel, "bytes_per_step": step_bytes,
                    "ring_buffer_sets": int(ring), "ring_bytes": int(ring * set_bytes)},
         "elements_per_s": round(numel / sec_per_step, 1),
         "host_enqueue_us_per_step": round((t_enq - t0) / args.steps * 1e6, 2),

@@ -105,12 +105,26 @@ _lib.fq_status_string.argtypes = [ctypes.c_int]
 _lib.fq_status_string.restype = ctypes.c_char_p
 
 
+class FqTensorArray:
+    """A host array of descriptors marshalled once (`fq_tensor_array`) and reused across calls."""
+
+    def __init__(self, tensors):
+        tensors = list(tensors)
+        self.n = len(tensors)
+        self.array = (FqTensor * max(1, self.n))(*tensors)
+
+
+def fq_tensor_array(tensors) -> FqTensorArray:
+    return FqTensorArray(tensors)
+
+
 def _array(tensors):
+    if isinstance(tensors, FqTensorArray):
+        return tensors.array, tensors.n
     if isinstance(tensors, FqTensor):
         tensors = [tensors]
-    tensors = list(tensors)
-    arr = (FqTensor * max(1, len(tensors)))(*tensors)
-    return arr, len(tensors)
+    a = FqTensorArray(tensors)
+    return a.array, a.n
 
 
 def _stream(stream):

@@ -254,27 +254,40 @@ template <typename T> __device__ __forceinline__ int head_elems(const void *p, i
     return h < n ? h : n;
 }
 
-// Scale of this block's channel: one wavefront evaluates Eq. (3)-(4), everyone reads it from LDS.
-// Callers issue their first global loads before this, so the evaluation and the barrier sit in
-// the shadow of the memory latency.  The evaluating wavefront rotates with the block index:
-// wavefront w of a block runs on SIMD w of its compute unit, and a few hundred binary64
-// instructions per resident block would otherwise all queue on SIMD 0.
+// Scale of this block's channel.  Callers issue their first global loads before this, so the
+// evaluation sits in the shadow of the memory latency.  FQ_SCALE_PER_WAVE = 1: every wavefront
+// evaluates Eq. (3)-(4) for itself (about a hundred binary64 instructions, no barrier, no LDS);
+// 0: one wavefront (rotating with the block index, so the work spreads over the four SIMDs of a
+// compute unit) evaluates it and the others read it from LDS after a barrier.
+#ifndef FQ_SCALE_PER_WAVE
+#define FQ_SCALE_PER_WAVE 0
+#endif
 template <bool NEED_SIGMOID>
-__device__ __forceinline__ QParams block_params(const DevTensor &d, float theta, BlockScale *shared_scale)
+__device__ __forceinline__ QParams block_params(const DevTensor &d, float theta, BlockScale &bs)
 {
+#if FQ_SCALE_PER_WAVE
+    const Scale sc = compute_scale<NEED_SIGMOID>(theta, d.eps, d.s_min, d.s_max);
+    bs.s = sc.s;
+    bs.rd = 1.0 / (double)sc.s;
+    bs.sigmoid = sc.sigmoid;
+    bs.clip_active = sc.clip_active ? 1u : 0u;
+#else
+    __shared__ BlockScale shared_scale;
     if ((threadIdx.x >> 6) == (blockIdx.x & (kBlock / 64 - 1))) {
         const Scale sc = compute_scale<NEED_SIGMOID>(theta, d.eps, d.s_min, d.s_max);
         if ((threadIdx.x & 63) == 0) {
-            shared_scale->s = sc.s;
-            shared_scale->rd = 1.0 / (double)sc.s;
-            shared_scale->sigmoid = sc.sigmoid;
-            shared_scale->clip_active = sc.clip_active ? 1u : 0u;
+            shared_scale.s = sc.s;
+            shared_scale.rd = 1.0 / (double)sc.s;
+            shared_scale.sigmoid = sc.sigmoid;
+            shared_scale.clip_active = sc.clip_active ? 1u : 0u;
         }
     }
     __syncthreads();
+    bs = shared_scale;
+#endif
     QParams p;
-    p.rd = shared_scale->rd;
-    p.s = shared_scale->s;
+    p.rd = bs.rd;
+    p.s = bs.s;
     p.lo = d.lo;
     p.hi = d.hi;
     return p;
@@ -321,8 +334,8 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
         }
     }
 
-    __shared__ BlockScale shared_scale;
-    const QParams p = block_params<false>(d, theta, &shared_scale);
+    BlockScale bs;
+    const QParams p = block_params<false>(d, theta, bs);
     if (d.s && ck.first == (long long)ck.channel * d.inner && tid == 0) st_global(d.s + ck.channel, p.s);
 
     for (int v0 = 0; v0 < nvec;) {
@@ -375,7 +388,7 @@ __device__ __forceinline__ double backward_elem(const T *x, const T *gy, T *gx, 
 
 // Per-thread sum of gy*t over this thread's elements of the chunk (binary64).
 template <typename T, bool WRITE_GX>
-__device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk &ck, BlockScale *shared_scale)
+__device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk &ck, BlockScale &bs)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
@@ -406,7 +419,7 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
         }
     }
 
-    const QParams p = block_params<true>(d, theta, shared_scale);
+    const QParams p = block_params<true>(d, theta, bs);
 
     double acc[kUnroll];
 #pragma unroll
@@ -453,17 +466,17 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
 }
 
 // Chain rule through Eq. (3)-(4) and the per-channel outputs of the backward pass.
-__device__ __forceinline__ void write_channel_grads(const DevTensor &d, unsigned c, double total, const BlockScale *bs)
+__device__ __forceinline__ void write_channel_grads(const DevTensor &d, unsigned c, double total, const BlockScale &bs)
 {
     if (d.gs) st_global(d.gs + c, (float)total);
-    if (d.gtheta) st_global(d.gtheta + c, bs->clip_active ? 0.0f : (float)(total * bs->sigmoid));
-    if (d.s) st_global(d.s + c, bs->s);
+    if (d.gtheta) st_global(d.gtheta + c, bs.clip_active ? 0.0f : (float)(total * bs.sigmoid));
+    if (d.s) st_global(d.s + c, bs.s);
 }
 
 // Sum the per-block partials of channel c in a fixed order (thread-strided binary64 sums, fixed
 // tree).  Block-wide; lds holds kBlock/64 doubles.  Partials are read with agent-scope loads:
 // they may have been written by a block running on another XCD, whose L2 is not this one.
-__device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c, const BlockScale *bs, double *lds)
+__device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c, const BlockScale &bs, double *lds)
 {
     const unsigned bpc = d.outer * d.cps;
     double acc = 0.0;
@@ -504,11 +517,11 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
     __shared__ double wave_part[kBlock / 64];
     __shared__ double fin_part[kBlock / 64];
     __shared__ unsigned is_last;
-    __shared__ BlockScale shared_scale;
 
     const Chunk ck = locate_chunk(d, local_block);
     const bool write_gx = !(d.flags & 1u);
-    double sum = write_gx ? backward_chunk<T, true>(d, ck, &shared_scale) : backward_chunk<T, false>(d, ck, &shared_scale);
+    BlockScale bs;
+    double sum = write_gx ? backward_chunk<T, true>(d, ck, bs) : backward_chunk<T, false>(d, ck, bs);
 
     sum = wave_sum(sum);
     if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = sum;
@@ -522,7 +535,7 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
         if (!FUSED) {
             __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else if (bpc == 1u) {
-            write_channel_grads(d, ck.channel, total, &shared_scale);
+            write_channel_grads(d, ck.channel, total, bs);
         } else if (bpc == 2u) {
             unsigned long long mine = __builtin_bit_cast(unsigned long long, total);
             if (mine == 0ull) mine = 0x8000000000000000ull;
@@ -531,7 +544,7 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
             if (theirs != 0ull) {
                 __hip_atomic_store(&d.slot[ck.channel], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const double both = (__builtin_bit_cast(double, theirs) + total) + 0.0;
-                write_channel_grads(d, ck.channel, both, &shared_scale);
+                write_channel_grads(d, ck.channel, both, bs);
             }
         } else {
             // Agent-scope store: written through to where every XCD can see it.  Wait until it
@@ -552,7 +565,7 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
         if (is_last) {
             // every other block of this channel completed its partial store before its ticket
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            finalize_channel(d, ck.channel, &shared_scale, fin_part);
+            finalize_channel(d, ck.channel, bs, fin_part);
         }
     }
 }
@@ -628,12 +641,12 @@ __global__ void __launch_bounds__(kBlock) backward_multi_kernel(const DevTensor 
 __global__ void __launch_bounds__(kBlock) finalize_kernel(const KArgs a)
 {
     __shared__ double fin_part[kBlock / 64];
-    __shared__ BlockScale shared_scale;
     const DevTensor d = a.table ? fetch(a.table, find_by_channel((const FQ_CONST DevTensor *)a.table, a.n, blockIdx.x))
                                 : a.one;
     const unsigned c = blockIdx.x - d.chan_begin;
-    block_params<true>(d, ld_uniform(d.theta + c), &shared_scale);
-    finalize_channel(d, c, &shared_scale, fin_part);
+    BlockScale bs;
+    block_params<true>(d, ld_uniform(d.theta + c), bs);
+    finalize_channel(d, c, bs, fin_part);
 }
 
 // s[c] for every channel; used when a tensor has channels but no elements (forward)
