@@ -129,6 +129,26 @@ fq_status fq_backward(const fq_tensor *t, void *workspace, size_t ws_bytes, void
 fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode,
                           void *workspace, size_t ws_bytes, void *hip_stream);
 
+/*
+ * The same multi-tensor launch, prepared once and replayed: the front end's tensor list is
+ * static (the same 22 layers every frame, Sec. 4.3.4), so validation, chunk planning and the
+ * copy of the descriptor table need not be repeated per call.
+ *
+ * fq_plan_create validates `ts` exactly as fq_multi_tensor does, copies the descriptor table to
+ * the head of `workspace` on `stream` and returns a host-side plan.  fq_plan_run enqueues the
+ * kernel(s) on `stream` and nothing else (no copy, no host allocation), so it may be captured in
+ * a HIP graph.  The plan keeps the device pointers it was created with: the tensors and the
+ * workspace must stay allocated at the same addresses, the workspace must not be written by
+ * anything else (one workspace per plan; zero it before fq_plan_create for backward plans), and
+ * fq_plan_run must be ordered after fq_plan_create's stream work.  Tensor contents and theta may
+ * change freely between runs.  fq_plan_destroy frees the host-side plan only (NULL is allowed).
+ */
+typedef struct fq_plan fq_plan;
+fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,
+                         void *hip_stream, fq_plan **plan);
+fq_status fq_plan_run(const fq_plan *plan, void *hip_stream);
+void fq_plan_destroy(fq_plan *plan);
+
 /* Static, NUL-terminated description of a status code. */
 const char *fq_status_string(fq_status status);
 

@@ -101,6 +101,13 @@ _lib.fq_backward.restype = ctypes.c_int
 _lib.fq_multi_tensor.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_int, ctypes.c_int,
                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fq_multi_tensor.restype = ctypes.c_int
+_lib.fq_plan_create.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
+_lib.fq_plan_create.restype = ctypes.c_int
+_lib.fq_plan_run.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+_lib.fq_plan_run.restype = ctypes.c_int
+_lib.fq_plan_destroy.argtypes = [ctypes.c_void_p]
+_lib.fq_plan_destroy.restype = None
 _lib.fq_status_string.argtypes = [ctypes.c_int]
 _lib.fq_status_string.restype = ctypes.c_char_p
 
@@ -180,3 +187,20 @@ def fq_multi_tensor(tensors, mode, workspace, stream=None):
     arr, n = _array(tensors)
     p, nbytes = _ws(workspace)
     _check(_lib.fq_multi_tensor(arr, n, mode, p, nbytes, _stream(stream)))
+
+
+def fq_plan_create(tensors, mode, workspace, stream=None):
+    """Returns an opaque plan handle (ctypes.c_void_p); release it with fq_plan_destroy."""
+    arr, n = _array(tensors)
+    p, nbytes = _ws(workspace)
+    plan = ctypes.c_void_p()
+    _check(_lib.fq_plan_create(arr, n, mode, p, nbytes, _stream(stream), ctypes.byref(plan)))
+    return plan
+
+
+def fq_plan_run(plan, stream=None):
+    _check(_lib.fq_plan_run(plan, _stream(stream)))
+
+
+def fq_plan_destroy(plan):
+    _lib.fq_plan_destroy(plan)

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <new>
 #include <vector>
 
 #include "../../include/fq.h"
@@ -237,12 +238,25 @@ bool any_flag(const fq_tensor *ts, int n, unsigned flag)
     return false;
 }
 
-fq_status run(const fq_tensor *ts, int n, int mode, bool use_table, void *workspace, size_t ws_bytes,
-              void *stream)
+// Everything a launch needs once the descriptors have been validated and laid out.
+struct Prepared {
+    KArgs args;
+    int mode = 0;
+    long long blocks = 0, channels = 0;
+    bool emit_q = false, two_pass = false, any_empty_with_channels = false;
+};
+
+// Validate, plan, build the device descriptors and (for table launches) copy them to the head of
+// the workspace.  Nothing is launched.
+fq_status prepare(const fq_tensor *ts, int n, int mode, bool use_table, void *workspace, size_t ws_bytes,
+                  void *stream, Prepared &P)
 {
     Layout L;
     fq_status st = make_layout(ts, n, mode, L);
     if (st != FQ_OK) return st;
+    std::memset(&P.args, 0, sizeof P.args);
+    P.args.n = n;
+    P.mode = mode;
     if (n == 0) return FQ_OK;
     const bool need_ws = use_table || mode == FQ_MODE_BACKWARD;
     if (need_ws) {
@@ -251,34 +265,45 @@ fq_status run(const fq_tensor *ts, int n, int mode, bool use_table, void *worksp
     }
     std::vector<DevTensor> table;
     build_table(ts, n, L, (char *)workspace, table);
-
-    KArgs a;
-    std::memset(&a, 0, sizeof a);
-    a.n = n;
     if (use_table) {
-        a.table = (const DevTensor *)workspace;
+        P.args.table = (const DevTensor *)workspace;
         if (copy_table_async(workspace, table.data(), (size_t)n * sizeof(DevTensor), stream) != 0)
             return FQ_ERR_LAUNCH;
     } else {
-        a.one = table[0];
+        P.args.one = table[0];
     }
+    P.blocks = L.blocks;
+    P.channels = L.channels;
+    P.any_empty_with_channels = L.any_empty_with_channels;
+    for (int i = 0; i < n; ++i) P.emit_q = P.emit_q || ts[i].q != nullptr;
+    P.two_pass = any_flag(ts, n, FQ_FLAG_TWO_PASS) || L.any_empty_with_channels;
+    return FQ_OK;
+}
 
-    if (mode == FQ_MODE_FORWARD) {
-        bool emit_q = false;
-        for (int i = 0; i < n; ++i) emit_q = emit_q || ts[i].q != nullptr;
-        if (L.blocks > 0 && launch_forward(a, (unsigned)L.blocks, emit_q, stream) != 0) return FQ_ERR_LAUNCH;
+fq_status launch_prepared(const Prepared &P, void *stream)
+{
+    if (P.args.n == 0) return FQ_OK;
+    if (P.mode == FQ_MODE_FORWARD) {
+        if (P.blocks > 0 && launch_forward(P.args, (unsigned)P.blocks, P.emit_q, stream) != 0) return FQ_ERR_LAUNCH;
         // tensors without elements never reach a block: write the scales of all channels in a
         // separate small launch (same values as the main kernel writes)
-        if (L.any_empty_with_channels && launch_scale_only(a, (unsigned)L.channels, stream) != 0)
+        if (P.any_empty_with_channels && launch_scale_only(P.args, (unsigned)P.channels, stream) != 0)
             return FQ_ERR_LAUNCH;
         return FQ_OK;
     }
-
-    const bool two_pass = any_flag(ts, n, FQ_FLAG_TWO_PASS) || L.any_empty_with_channels;
-    if (L.blocks > 0 && launch_backward(a, (unsigned)L.blocks, !two_pass, stream) != 0) return FQ_ERR_LAUNCH;
-    if (two_pass && L.channels > 0 && launch_finalize(a, (unsigned)L.channels, stream) != 0)
+    if (P.blocks > 0 && launch_backward(P.args, (unsigned)P.blocks, !P.two_pass, stream) != 0) return FQ_ERR_LAUNCH;
+    if (P.two_pass && P.channels > 0 && launch_finalize(P.args, (unsigned)P.channels, stream) != 0)
         return FQ_ERR_LAUNCH;
     return FQ_OK;
+}
+
+fq_status run(const fq_tensor *ts, int n, int mode, bool use_table, void *workspace, size_t ws_bytes,
+              void *stream)
+{
+    Prepared P;
+    fq_status st = prepare(ts, n, mode, use_table, workspace, ws_bytes, stream, P);
+    if (st != FQ_OK) return st;
+    return launch_prepared(P, stream);
 }
 
 }  // namespace
@@ -329,6 +354,34 @@ fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode, void *workspace,
 {
     return fq::run(ts, n, mode, true, workspace, ws_bytes, hip_stream);
 }
+
+struct fq_plan {
+    fq::Prepared prepared;
+};
+
+fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,
+                         void *hip_stream, fq_plan **plan)
+{
+    if (!plan) return FQ_ERR_NULL;
+    *plan = nullptr;
+    fq_plan *p = new (std::nothrow) fq_plan();
+    if (!p) return FQ_ERR_LAUNCH;
+    fq_status st = fq::prepare(ts, n, mode, true, workspace, ws_bytes, hip_stream, p->prepared);
+    if (st != FQ_OK) {
+        delete p;
+        return st;
+    }
+    *plan = p;
+    return FQ_OK;
+}
+
+fq_status fq_plan_run(const fq_plan *plan, void *hip_stream)
+{
+    if (!plan) return FQ_ERR_NULL;
+    return fq::launch_prepared(plan->prepared, hip_stream);
+}
+
+void fq_plan_destroy(fq_plan *plan) { delete plan; }
 
 const char *fq_status_string(fq_status status)
 {

@@ -67,6 +67,50 @@ def test_multi_equals_single_calls_bitwise():
 
 
 @pytest.mark.timeout(600)
+def test_plan_replay_equals_direct_calls_bitwise():
+    """fq_plan_create once, fq_plan_run several times with changing data and theta: every replay
+    equals a fresh fq_multi_tensor call bit for bit (and the oracle once)."""
+    cases = workloads.multi_tensor_mixed(n_act=5, n_wgt=3, target_bytes=8 << 20, max_batch=2)
+    H.say("multi/plan: %d tensors" % len(cases))
+    dcs = [H.DeviceCase(c, want_q=False) for c in cases]
+    arr = fq.fq_tensor_array([d.desc for d in dcs])
+    ws_f = H.workspace_for(arr, fq.FQ_MODE_FORWARD)
+    ws_b = H.workspace_for(arr, fq.FQ_MODE_BACKWARD)
+    plan_f = fq.fq_plan_create(arr, fq.FQ_MODE_FORWARD, ws_f)
+    plan_b = fq.fq_plan_create(arr, fq.FQ_MODE_BACKWARD, ws_b)
+    ws_ref = H.workspace_for(arr, fq.FQ_MODE_BACKWARD)
+    try:
+        for rep in range(3):
+            if rep:
+                for d in dcs:                       # new data, new theta, same addresses
+                    d.x.mul_(1.25)
+                    d.theta.add_(0.01 * rep)
+            fq.fq_plan_run(plan_f)
+            fq.fq_plan_run(plan_b)
+            torch.cuda.synchronize()
+            got = [[getattr(d, k).clone() for k in ("y", "gx", "gs", "gtheta", "s")] for d in dcs]
+            if rep == 0:
+                for i, (c, d) in enumerate(zip(cases, dcs)):
+                    ref = H.oracle_forward(c)
+                    H.check_forward(d, ref, "plan[%d] fwd" % i)
+                    H.check_backward(d, ref[0], ref[1], "plan[%d] bwd" % i)
+            for d in dcs:
+                for k in ("y", "gx"):
+                    getattr(d, k).zero_()
+                for k in ("gs", "gtheta", "s"):
+                    getattr(d, k).fill_(float("nan"))
+            fq.fq_multi_tensor(arr, fq.FQ_MODE_FORWARD, ws_ref)
+            fq.fq_multi_tensor(arr, fq.FQ_MODE_BACKWARD, ws_ref)
+            torch.cuda.synchronize()
+            for d, g in zip(dcs, got):
+                for k, t in zip(("y", "gx", "gs", "gtheta", "s"), g):
+                    assert torch.equal(getattr(d, k).view(torch.uint8), t.view(torch.uint8)), (rep, k)
+    finally:
+        fq.fq_plan_destroy(plan_f)
+        fq.fq_plan_destroy(plan_b)
+
+
+@pytest.mark.timeout(600)
 def test_full_size_list_about_1GiB():
     """The 64-tensor, ~1 GiB list in the launch configuration used for timing: one forward launch
     and one backward launch, every element checked against the oracle."""

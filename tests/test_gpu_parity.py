@@ -73,6 +73,14 @@ def test_train_batch_fp16_reduced():
     _fwd_bwd(case, "train_batch_fp16/reduced")
 
 
+@pytest.mark.timeout(600)
+def test_train_batch_fp16_full_size():
+    """15x128x120x160 FP16, the reduction runs over 15 frames x 2 chunks = 30 blocks per channel."""
+    case = workloads.make("train_batch_fp16")[0]
+    info = _fwd_bwd(case, "train_batch_fp16 15x128x120x160", want_q=False)
+    assert info["y_exact"]
+
+
 @pytest.mark.parametrize("dtype", [np.float16, np.float32])
 @pytest.mark.parametrize("inner", [1, 7, 8, 9, 147, 1023, 8191, 8200, 20001])
 def test_odd_inner_and_misaligned_slabs(dtype, inner):
