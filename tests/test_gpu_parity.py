@@ -256,3 +256,55 @@ def test_backward_is_bitwise_reproducible():
                 first = out
             for a, b in zip(first, out):
                 assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), (flags, rep)
+
+
+@pytest.mark.timeout(600)
+def test_more_than_2_31_elements():
+    """One per-tensor FP16 tensor of 2^31 + 4099 elements (64-bit element offsets, 209 719 blocks,
+    as many partial sums for one channel).  Outputs are checked against the oracle on slices
+    (a per-tensor scale makes every slice a valid tensor of its own): the head, a window across
+    element 2^31, the ragged tail, and windows at odd offsets; the scale gradient of the whole
+    tensor is checked against the binary64 sum of the scale gradients of eight pieces."""
+    from oracle import fq_oracle
+    n = (1 << 31) + 4099
+    H.say("large tensor: %d FP16 elements" % n)
+    g = torch.Generator(device="cuda").manual_seed(20251112)
+    x = torch.empty(n, dtype=torch.float16, device="cuda")
+    gy = torch.empty(n, dtype=torch.float16, device="cuda")
+    step = 1 << 28
+    for a in range(0, n, step):
+        b = min(n, a + step)
+        x[a:b] = torch.randn(b - a, generator=g, device="cuda", dtype=torch.float32).mul_(3.0)
+        gy[a:b] = torch.randn(b - a, generator=g, device="cuda", dtype=torch.float32)
+    y, gx = torch.empty_like(x), torch.empty_like(x)
+    theta_h = workloads.theta_for_scale([0.05])
+    theta = H.dev(theta_h)
+    s, gs, gt = (torch.full((1,), float("nan"), device="cuda") for _ in range(3))
+    d = fq.FqTensor.from_torch(1, 1, n, -128, 127, x=x, y=y, theta=theta, s=s, gy=gy, gx=gx, gs=gs, gtheta=gt)
+    ws = H.workspace_for(d, fq.FQ_MODE_BACKWARD)
+    fq.fq_forward(d)
+    fq.fq_backward(d, ws)
+    torch.cuda.synchronize()
+    so, active = fq_oracle.scale(theta_h)
+    assert np.array_equal(s.cpu().numpy(), so)
+    windows = [(0, 1 << 20), ((1 << 31) - (1 << 19), n), (123457, 123457 + 300001),
+               ((1 << 30) + 7, (1 << 30) + 7 + 262147), (n - 4099 - 1283, n - 5)]
+    for a, b in windows:
+        H.say("  window [%d, %d)" % (a, b))
+        xs, gys = x[a:b].cpu().numpy(), gy[a:b].cpu().numpy()
+        yo, _ = fq_oracle.forward(xs, so, -128, 127, 1, 1, b - a, want_q=False)
+        ro = fq_oracle.backward(xs, gys, so, theta_h, active, -128, 127, 1, 1, b - a)
+        assert np.array_equal(y[a:b].cpu().numpy().view(np.uint16), yo.view(np.uint16))
+        assert np.array_equal(gx[a:b].cpu().numpy().view(np.uint16), ro["gx"].view(np.uint16))
+    # whole-tensor scale gradient vs eight pieces run separately
+    total, pieces = float(gs.item()), []
+    cut = [0] + [k * (n // 8) + 3 * k for k in range(1, 8)] + [n]
+    gsp = torch.empty(1, device="cuda")
+    for a, b in zip(cut[:-1], cut[1:]):
+        dp = fq.FqTensor.from_torch(1, 1, b - a, -128, 127, x=x[a:b], theta=theta, gy=gy[a:b], gs=gsp,
+                                    flags=fq.FQ_FLAG_NO_DX)
+        wsp = H.workspace_for(dp, fq.FQ_MODE_BACKWARD)
+        fq.fq_backward(dp, wsp)
+        torch.cuda.synchronize()
+        pieces.append(float(gsp.item()))
+    assert abs(total - sum(pieces)) <= 1e-6 * sum(abs(p) for p in pieces), (total, pieces)
