@@ -9,8 +9,12 @@ the 256 MB Infinity Cache, so every step streams from HBM rather than from cache
 
 Prints one JSON line: whole-job GB/s (algorithmic bytes: forward 2b + backward 3b per element),
 the roofline position of the dominant kernel (the backward kernel, 3b bytes per element, timed
-in every step of the timed region by HIP events that ride on the kernel's own dispatch) and the
-CPU oracle timed on this host beside it.
+inside the timed region with HIP events on the launch stream) and the CPU oracle timed on this
+host beside it.
+
+Other workloads (--workload) and the int8 code-emission forward (--pass codes: x in, packed int8
+codes out, b+1 bytes per element) use the same machinery; lists of tensors go through the
+multi-tensor entry points, one launch per pass.
 """
 import argparse
 import ctypes
@@ -32,15 +36,14 @@ EVENT_EVERY = 8                # one bracketed step in this many
 TRAFFIC_BYTES_PER_LAUNCH = 44445594
 
 WORKLOAD_TEXT = {
-    "act_fp32_per_tensor": "act_fp32_per_tensor: FP32 1x128x30x40, one scale, codes -128..127, forward + STE backward",
+    "act_fp32_per_tensor": "act_fp32_per_tensor: FP32 1x128x30x40, one scale, codes -128..127",
     "feature_fp16_per_channel": "feature_fp16_per_channel: FP16 1x384x120x160 NCHW, 384 per-channel scales, "
-                                "codes -128..127, forward + STE backward",
+                                "codes -128..127",
     "conv_weights_fp32": "conv_weights_fp32: FP32 384x384x3x3 + 128x128x3x3, per-output-channel scales, codes "
-                         "-127..127, forward + STE backward, one multi-tensor launch per pass",
-    "train_batch_fp16": "train_batch_fp16: FP16 15x128x120x160, 128 per-channel scales, codes -128..127, "
-                        "forward + STE backward",
+                         "-127..127, one multi-tensor launch per pass",
+    "train_batch_fp16": "train_batch_fp16: FP16 15x128x120x160, 128 per-channel scales, codes -128..127",
     "multi_tensor_mixed": "multi_tensor_mixed: 64 mixed FP16/FP32, 4/8-bit, per-tensor/per-channel tensors, "
-                          "about 1 GiB of inputs, forward + STE backward, one multi-tensor launch per pass",
+                          "about 1 GiB of inputs, one multi-tensor launch per pass",
 }
 
 
@@ -51,14 +54,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="feature_fp16_per_channel",
                     help="one of paper_2511_12653_amd.workloads.WORKLOAD_NAMES (default: the headline "
-                         "tensor); lists of tensors go through fq_multi_tensor, one launch per pass")
+                         "tensor); lists of tensors go through the multi-tensor entry points")
+    ap.add_argument("--pass", dest="which", default="train", choices=["train", "codes"],
+                    help="train: forward + STE backward (default); codes: forward that writes only the "
+                         "packed int8 codes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
-                    help="after the timed region also run N plain device copies of the 14745600-byte "
-                         "x tensor (torch copy_), so that a rocprofv3 --pmc run of this command holds a "
-                         "copy kernel of known size to scale FETCH_SIZE / WRITE_SIZE by")
+                    help="after the timed region also run N plain device copies of the first tensor "
+                         "(torch copy_), so that a rocprofv3 --pmc run of this command holds a copy "
+                         "kernel of known size to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--no-kernel-events", action="store_true",
-                    help="do not attach timing events to the backward kernel (roofline becomes null)")
+                    help="put no timing events into the timed region (roofline becomes null)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (got --gpus %d); "
@@ -72,72 +78,96 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; there is no CPU fallback")
     torch.cuda.set_device(0)
-
     if args.workload not in workloads.WORKLOAD_NAMES:
-        sys.exit("bench.py: unknown workload %r (choose from %s)" % (args.workload, ", ".join(workloads.WORKLOAD_NAMES)))
+        sys.exit("bench.py: unknown workload %r (choose from %s)" % (
+            args.workload, ", ".join(workloads.WORKLOAD_NAMES)))
+    train = args.which == "train"
+
     cases = workloads.make(args.workload)
+    if not train:
+        cases = [cs for cs in cases if cs.qmin >= -128 and cs.qmax <= 127]
     multi = len(cases) > 1
     numel = sum(cs.numel for cs in cases)
     io_bytes = sum(cs.numel * cs.itemsize for cs in cases)        # sum over tensors of b * elements
-    set_bytes = 4 * io_bytes
+    set_bytes = 4 * io_bytes if train else io_bytes + numel
     ring = max(2, RING_BYTES // set_bytes) if set_bytes < RING_BYTES else 1
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
 
-    host = [(torch.from_numpy(cs.x.reshape(-1)), torch.from_numpy(cs.gy.reshape(-1)),
-             torch.from_numpy(cs.theta).cuda(), torch.empty(cs.channels, device="cuda"),
-             torch.empty(cs.channels, device="cuda")) for cs in cases]
-    descs, keep = [], []
+    # ---- device buffers: `ring` independent sets, descriptors marshalled once ------------------
+    per_case = [(torch.from_numpy(cs.x.reshape(-1)), torch.from_numpy(cs.gy.reshape(-1)),
+                 torch.from_numpy(cs.theta).cuda(), torch.empty(cs.channels, device="cuda"),
+                 torch.empty(cs.channels, device="cuda")) for cs in cases]
+    sets, keep, first_bufs = [], [], []
     for _ in range(ring):
         group = []
-        for cs, (hx, hg, theta, gs, gtheta) in zip(cases, host):
-            x, gy = hx.cuda(), hg.cuda()
-            y, gx = torch.empty_like(x), torch.empty_like(x)
-            keep.append((x, gy, y, gx))
-            group.append(fq.FqTensor.from_torch(cs.outer, cs.channels, cs.inner, cs.qmin, cs.qmax, x=x, y=y,
-                                                theta=theta, gy=gy, gx=gx, gs=gs, gtheta=gtheta,
-                                                eps=cs.eps, s_min=cs.s_min, s_max=cs.s_max, flags=cs.flags))
-        descs.append(fq.fq_tensor_array(group) if multi else group[0])
-    stream = torch.cuda.current_stream()
-    case, c, b = cases[0], cases[0].channels, cases[0].itemsize
-    ws = None
-    if not multi:
-        ws = torch.zeros(fq.fq_workspace_bytes(descs[0], fq.FQ_MODE_BACKWARD) // 4, dtype=torch.int32,
-                         device="cuda")
+        for j, (cs, (hx, hg, theta, gs, gtheta)) in enumerate(zip(cases, per_case)):
+            common = dict(theta=theta, eps=cs.eps, s_min=cs.s_min, s_max=cs.s_max, flags=cs.flags)
+            x = hx.cuda()
+            if train:
+                gy = hg.cuda()
+                y, gx = torch.empty_like(x), torch.empty_like(x)
+                keep.append((x, y, gy, gx))
+                group.append(fq.FqTensor.from_torch(cs.outer, cs.channels, cs.inner, cs.qmin, cs.qmax, x=x,
+                                                    y=y, gy=gy, gx=gx, gs=gs, gtheta=gtheta, **common))
+            else:
+                q = torch.empty(cs.numel, dtype=torch.int8, device="cuda")
+                y = torch.empty_like(x) if (j == 0 and args.copy_calibration) else None
+                keep.append((x, q, y))
+                group.append(fq.FqTensor.from_torch(cs.outer, cs.channels, cs.inner, cs.qmin, cs.qmax, x=x,
+                                                    q=q, s=gs, **common))
+            if j == 0:
+                first_bufs.append((x, y))
+        sets.append(fq.fq_tensor_array(group) if multi else group[0])
 
+    def zeros(nbytes):
+        t = torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda")
+        keep.append(t)
+        return t
+
+    # ---- the launches of one step ---------------------------------------------------------------
     if multi:
-        # a static tensor list: prepare once (descriptor table resident in a workspace of its
-        # own per plan), then each pass is one kernel launch and nothing else
-        plans = {}
-        for k, d in enumerate(descs):
-            wf = torch.zeros(fq.fq_workspace_bytes(d, fq.FQ_MODE_FORWARD) // 4, dtype=torch.int32, device="cuda")
-            wb = torch.zeros(fq.fq_workspace_bytes(d, fq.FQ_MODE_BACKWARD) // 4, dtype=torch.int32, device="cuda")
-            keep.append((wf, wb))
-            plans[k] = (fq.fq_plan_create(d, fq.FQ_MODE_FORWARD, wf, stream),
-                        fq.fq_plan_create(d, fq.FQ_MODE_BACKWARD, wb, stream))
-        descs = list(range(len(descs)))
+        # a static tensor list: prepare once (descriptor table resident in a workspace of its own
+        # per plan), then each pass is one kernel launch and nothing else
+        plans = []
+        for d in sets:
+            pf = fq.fq_plan_create(d, fq.FQ_MODE_FORWARD, zeros(fq.fq_workspace_bytes(d, fq.FQ_MODE_FORWARD)), stream)
+            pb = None
+            if train:
+                pb = fq.fq_plan_create(d, fq.FQ_MODE_BACKWARD, zeros(fq.fq_workspace_bytes(d, fq.FQ_MODE_BACKWARD)),
+                                       stream)
+            plans.append((pf, pb))
 
-        def run_forward(k):
+        def forward(k):
             fq.fq_plan_run(plans[k][0], stream)
 
-        def run_backward(k):
+        def backward(k):
             fq.fq_plan_run(plans[k][1], stream)
     else:
-        def run_forward(d):
-            fq.fq_forward(d, stream)
+        ws = zeros(fq.fq_workspace_bytes(sets[0], fq.FQ_MODE_BACKWARD)) if train else None
 
-        def run_backward(d):
-            fq.fq_backward(d, ws, stream)
+        def forward(k):
+            fq.fq_forward(sets[k], stream)
 
-    # Kernel timing inside the timed region, with raw HIP events on the launch stream.  A pair of
-    # event records costs the queue about as much as a small kernel, so (a) only every
-    # EVENT_EVERY-th step carries a pair, and (b) the backward kernel's duration is taken as a
-    # difference that cancels the pair's own overhead: steps of kind A bracket forward+backward,
-    # steps of kind B bracket the forward alone, and  t(backward) = mean(A) - mean(B).
+        def backward(k):
+            fq.fq_backward(sets[k], ws, stream)
+
+    def launches_of_step(i):
+        k = i % ring
+        return [(forward, k), (backward, k)] if train else [(forward, k)]
+
+    # ---- kernel timing inside the timed region --------------------------------------------------
+    # Raw HIP events on the launch stream.  A pair of event records costs the queue about as much
+    # as a small kernel, so (a) only every EVENT_EVERY-th step carries a pair and (b) the timed
+    # kernel's duration is a difference that cancels the pair's own cost: brackets of kind A span
+    # two consecutive launches, brackets of kind B only the first of them, and
+    # t(second launch) = mean(A) - mean(B).  In a training step the second launch is the backward
+    # kernel; in the codes pass it is the next step's forward kernel.
     hip = ctypes.CDLL("libamdhip64.so")
     hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
     hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
     hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
-    sp = stream.cuda_stream
 
     def new_event():
         e = ctypes.c_void_p()
@@ -145,69 +175,76 @@ def main():
             sys.exit("bench.py: hipEventCreate failed")
         return e
 
-    def step(i, ev=None, kind=None):
-        d = descs[i % ring]
-        if ev is not None:
-            hip.hipEventRecord(ev[0], sp)
-        run_forward(d)
-        if kind == "fwd":
-            hip.hipEventRecord(ev[1], sp)
-        run_backward(d)
-        if kind == "fwd+bwd":
-            hip.hipEventRecord(ev[1], sp)
-
-    for i in range(args.warmup):
-        step(i)
-    events = {}
+    timed = []
+    for i in range(args.steps):
+        timed.extend(launches_of_step(args.warmup + i))
+    per_step = len(timed) // args.steps
+    record_before = {}                      # launch index -> events to record just before it
+    brackets = []
     if not args.no_kernel_events:
         for n, i in enumerate(range(EVENT_EVERY - 1, args.steps, EVENT_EVERY)):
-            events[i] = ((new_event(), new_event()), "fwd+bwd" if n % 2 == 0 else "fwd")
+            first = i * per_step
+            span = 2 if n % 2 == 0 else 1
+            if first + span > len(timed):
+                break
+            a, z = new_event(), new_event()
+            record_before.setdefault(first, []).append(a)
+            record_before.setdefault(first + span, []).append(z)
+            brackets.append((a, z, span))
+
+    for i in range(args.warmup):
+        for fn, k in launches_of_step(i):
+            fn(k)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        if i in events:
-            step(args.warmup + i, *events[i])
-        else:
-            step(args.warmup + i)
+    for idx, (fn, k) in enumerate(timed):
+        for e in record_before.get(idx, ()):
+            hip.hipEventRecord(e, sp)
+        fn(k)
+    for e in record_before.get(len(timed), ()):
+        hip.hipEventRecord(e, sp)
     t_enq = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
     for i in range(args.copy_calibration):
-        x, _, y, _ = keep[i % ring]
+        x, y = first_bufs[i % ring]
         y.copy_(x)
     torch.cuda.synchronize()
 
     sec_per_step = (t1 - t0) / args.steps
-    step_bytes = 5 * io_bytes
+    step_bytes = 5 * io_bytes if train else io_bytes + numel
     value = step_bytes / sec_per_step / 1e9
 
     roofline = None
-    if events:
-        dur = {"fwd+bwd": [], "fwd": []}
-        for (a, z), kind in events.values():
+    if brackets:
+        dur = {1: [], 2: []}
+        for a, z, span in brackets:
             ms = ctypes.c_float()
             if hip.hipEventElapsedTime(ctypes.byref(ms), a, z) != 0:
                 sys.exit("bench.py: hipEventElapsedTime failed")
-            dur[kind].append(ms.value * 1e-3)
+            dur[span].append(ms.value * 1e-3)
             hip.hipEventDestroy(a)
             hip.hipEventDestroy(z)
-        if dur["fwd"] and dur["fwd+bwd"]:
-            t_both, t_fwd = float(np.mean(dur["fwd+bwd"])), float(np.mean(dur["fwd"]))
-            t_bwd = t_both - t_fwd
-            bwd_bytes = 3 * io_bytes
-            achieved = bwd_bytes / t_bwd / 1e9
-            kname = "backward_multi_kernel<fused>" if multi else "backward_kernel<%s, fused>" % (
-                "f16" if b == 2 else "f32")
+        if dur[1] and dur[2]:
+            t_two, t_one = float(np.mean(dur[2])), float(np.mean(dur[1]))
+            t_kernel = t_two - t_one
+            kernel_bytes = 3 * io_bytes if train else io_bytes + numel
+            achieved = kernel_bytes / t_kernel / 1e9
+            dt = "f16" if cases[0].itemsize == 2 else "f32"
+            if train:
+                kname = "backward_multi_kernel<fused>" if multi else "backward_kernel<%s, fused>" % dt
+            else:
+                kname = "forward_multi_kernel<codes>" if multi else "forward_kernel<%s, codes>" % dt
+            headline = train and args.workload == "feature_fp16_per_channel"
             roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                        "traffic": TRAFFIC_BYTES_PER_LAUNCH if args.workload == "feature_fp16_per_channel" else None,
-                        "bytes_per_launch": bwd_bytes,
-                        "avg_us": round(t_bwd * 1e6, 2),
-                        "method": "HIP events on the launch stream in the timed region: mean(bracket "
-                                  "fwd+bwd) - mean(bracket fwd); cancels the event pair's own cost",
-                        "bracket_fwd_bwd_us": round(t_both * 1e6, 2), "bracket_fwd_us": round(t_fwd * 1e6, 2),
-                        "samples": [len(dur["fwd+bwd"]), len(dur["fwd"])]}
+                        "traffic": TRAFFIC_BYTES_PER_LAUNCH if headline else None,
+                        "bytes_per_launch": kernel_bytes, "avg_us": round(t_kernel * 1e6, 2),
+                        "method": "HIP events on the launch stream in the timed region: mean(bracket of two "
+                                  "launches) - mean(bracket of the first); cancels the event pair's own cost",
+                        "bracket_two_us": round(t_two * 1e6, 2), "bracket_one_us": round(t_one * 1e6, 2),
+                        "samples": [len(dur[2]), len(dur[1])]}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -220,30 +257,35 @@ def main():
                 break
             sample.append(cs)
             n_sample += cs.numel
-        sample_bytes = 5 * sum(cs.numel * cs.itemsize for cs in sample)
+        sample_bytes = sum((5 * cs.itemsize if train else cs.itemsize + 1) * cs.numel for cs in sample)
         reps, times = 3, []
         for _ in range(reps):
             c0 = time.perf_counter()
             for cs in sample:
                 s_, active = fq_oracle.scale(cs.theta, cs.eps, cs.s_min, cs.s_max)
-                fq_oracle.forward(cs.x, s_, cs.qmin, cs.qmax, cs.outer, cs.channels, cs.inner, want_q=False)
-                fq_oracle.backward(cs.x, cs.gy, s_, cs.theta, active, cs.qmin, cs.qmax,
-                                   cs.outer, cs.channels, cs.inner)
+                fq_oracle.forward(cs.x, s_, cs.qmin, cs.qmax, cs.outer, cs.channels, cs.inner, want_q=not train)
+                if train:
+                    fq_oracle.backward(cs.x, cs.gy, s_, cs.theta, active, cs.qmin, cs.qmax,
+                                       cs.outer, cs.channels, cs.inner)
             times.append(time.perf_counter() - c0)
         med = sorted(times)[len(times) // 2]
         cpu = {"value": round(sample_bytes / med / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-               "sample": "%d of %d tensors of the workload (%d elements, fwd+bwd), median of %d runs, "
-                         "%.2f s each" % (len(sample), len(cases), n_sample, reps, med),
+               "sample": "%d of %d tensors of the workload (%d elements, %s), median of %d runs, "
+                         "%.2f s each" % (len(sample), len(cases), n_sample,
+                                          "fwd+bwd" if train else "forward with codes", reps, med),
                "elements_per_s": round(n_sample / med, 1)}
 
     out = {
-        "metric": "fake-quant fwd+bwd GB/s", "value": round(value, 1), "unit": "GB/s",
+        "metric": "fake-quant fwd+bwd GB/s" if train else "fake-quant int8 code emission GB/s",
+        "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.workload], "tensors": len(cases),
-                   "launches_per_step": 2, "elements": numel, "bytes_per_step": step_bytes,
-                   "ring_buffer_sets": int(ring), "ring_bytes": int(ring * set_bytes)},
+        "config": {"workload": WORKLOAD_TEXT[args.workload] + (", forward + STE backward" if train
+                                                               else ", forward writing int8 codes only"),
+                   "tensors": len(cases), "launches_per_step": per_step, "elements": numel,
+                   "bytes_per_step": step_bytes, "ring_buffer_sets": int(ring),
+                   "ring_bytes": int(ring * set_bytes)},
         "elements_per_s": round(numel / sec_per_step, 1),
         "host_enqueue_us_per_step": round((t_enq - t0) / args.steps * 1e6, 2),
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),

@@ -72,8 +72,9 @@ typedef struct fq_tensor {
     float eps, s_min, s_max;          /* Eq. (3)-(4); plain softplus: eps = 0, s_min = FLT_MIN, s_max = +inf */
     uint32_t flags;                   /* FQ_FLAG_* */
     const void *x;                    /* in  (forward and backward) */
-    void *y;                          /* out (forward); may be exactly x (in place) */
-    int8_t *q;                        /* out (forward), optional: integer codes, 0 where x is NaN */
+    void *y;                          /* out (forward); may be exactly x (in place); may be NULL if q is given */
+    int8_t *q;                        /* out (forward), optional: integer codes (packed int8, one byte per
+                                         element, same [outer, channels, inner] order), 0 where x is NaN */
     const float *theta;               /* in  [channels], the learnable parameter ("log scale") */
     float *s;                         /* out [channels], optional: the scales used (forward and backward) */
     const void *gy;                   /* in  (backward): upstream gradient, same dtype/shape as x */
@@ -106,7 +107,10 @@ fq_status fq_workspace_init(void *workspace, size_t ws_bytes, void *hip_stream);
 
 /*
  * Forward, Eq. (3)-(5), one launch: reads x, theta; writes y and, if non-NULL, q and s.
- * A tensor with zero elements is a no-op (s is still written).
+ * With y = NULL and q != NULL only the integer codes are written (1 byte per element instead
+ * of 2 or 4): together with s they are the true-INT8 form of the tensor that the paper names as
+ * the deployment target (Sec. 3.1, 5.2).  A tensor with zero elements is a no-op (s is still
+ * written).
  */
 fq_status fq_forward(const fq_tensor *t, void *hip_stream);
 

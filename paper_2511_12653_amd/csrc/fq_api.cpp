@@ -99,7 +99,7 @@ fq_status validate_one(const fq_tensor &t, int mode, Plan &p)
     if (p.numel > 0 && !t.x) return FQ_ERR_NULL;
     if (!aligned(t.x, esz)) return FQ_ERR_ALIGN;
     if (mode == FQ_MODE_FORWARD) {
-        if (p.numel > 0 && !t.y) return FQ_ERR_NULL;
+        if (p.numel > 0 && !t.y && !t.q) return FQ_ERR_NULL;
         if (!aligned(t.y, esz)) return FQ_ERR_ALIGN;
         if (t.q && (t.qmin < -128 || t.qmax > 127)) return FQ_ERR_QRANGE;
         if (partial_overlap(t.x, t.y, bytes)) return FQ_ERR_ALIAS;

@@ -300,27 +300,34 @@ __device__ __forceinline__ void forward_elem(const T *x, T *y, int8_t *q, int i,
 {
     float qf;
     float yf = fq_value((float)ld_global(x + i), p, qf);
-    st_global(y + i, (T)yf);
+    if (y) st_global(y + i, (T)yf);
     if (EMIT_Q && q) st_global(q + i, code_of(qf));
 }
+
+// N int8 codes of one vector, packed: one 64-bit (FP16 input) or 32-bit (FP32 input) store.
+template <int N> struct CodeVec;
+template <> struct CodeVec<8> { typedef signed char type __attribute__((ext_vector_type(8))); };
+template <> struct CodeVec<4> { typedef signed char type __attribute__((ext_vector_type(4))); };
 
 template <typename T, bool EMIT_Q>
 __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local_block)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
+    typedef typename CodeVec<N>::type QV;
     const Chunk ck = locate_chunk(d, local_block);
     const T *x = (const T *)d.x + ck.first;
-    T *y = (T *)d.y + ck.first;
+    T *y = d.y ? (T *)d.y + ck.first : nullptr;          // NULL: integer codes only
     int8_t *q = (EMIT_Q && d.q) ? d.q + ck.first : nullptr;
     const int tid = threadIdx.x;
     const float theta = ld_uniform(d.theta + ck.channel);
 
-    const bool vector_ok = (((uintptr_t)x ^ (uintptr_t)y) & (kVecBytes - 1)) == 0;
+    const bool vector_ok = !y || (((uintptr_t)x ^ (uintptr_t)y) & (kVecBytes - 1)) == 0;
     const int head = vector_ok ? head_elems<T>(x, ck.n) : ck.n;
     const int nvec = (ck.n - head) / N;
     const VT *xv = (const VT *)(x + head);
-    VT *yv = (VT *)(y + head);
+    VT *yv = y ? (VT *)(y + head) : nullptr;
+    const bool q_packed = EMIT_Q && q && ((uintptr_t)(q + head) % N) == 0;
 
     // Issue the first row of loads (straight-line: out-of-range lanes re-read the last vector)
     // before the long binary64 scale evaluation, which then runs under the memory latency.
@@ -347,10 +354,17 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
                 float qf[N];
 #pragma unroll
                 for (int e = 0; e < N; ++e) o[e] = (T)fq_value((float)r[u][e], p, qf[e]);
-                st_stream(yv + v, o);
+                if (y) st_stream(yv + v, o);
                 if (EMIT_Q && q) {
+                    QV codes;
 #pragma unroll
-                    for (int e = 0; e < N; ++e) st_global(q + head + v * N + e, code_of(qf[e]));
+                    for (int e = 0; e < N; ++e) codes[e] = code_of(qf[e]);
+                    if (q_packed) {
+                        st_stream((QV *)(q + head + v * N), codes);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < N; ++e) st_global(q + head + v * N + e, (int8_t)codes[e]);
+                    }
                 }
             }
         }

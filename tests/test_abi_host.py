@@ -53,7 +53,7 @@ def test_validate_ok_and_status_strings(fq):
 
 
 @pytest.mark.parametrize("kw,mode,code", [
-    (dict(x=None), 1, -1), (dict(y=None), 1, -1), (dict(theta=None), 1, -1),
+    (dict(x=None), 1, -1), (dict(y=None), 1, -1), (dict(y=None, q=0x70000, qmax=300), 1, -4), (dict(theta=None), 1, -1),
     (dict(gy=None), 2, -1), (dict(gx=None), 2, -1),
     (dict(dtype=7), 1, -2),
     (dict(outer=-1), 1, -3), (dict(inner=1 << 62, outer=4), 1, -3), (dict(outer=1 << 31), 1, -3),
@@ -77,6 +77,7 @@ def test_validate_accepts_edge_cases(fq):
     assert fq.fq_validate(_desc(fq, outer=0, x=None, y=None), 1) == 0          # empty tensor
     assert fq.fq_validate(_desc(fq, channels=0, theta=None, x=None, y=None), 1) == 0
     assert fq.fq_validate(_desc(fq, qmin=-8, qmax=7), 1) == 0
+    assert fq.fq_validate(_desc(fq, y=None, q=0x70000), 1) == 0                 # codes only
     assert fq.fq_validate(_desc(fq, qmin=-127, qmax=127, q=0x70000), 1) == 0
     assert fq.fq_validate(_desc(fq, x=0x10002), 1) == 0                        # 2-byte aligned FP16
     assert fq.fq_validate([], 1) == 0

@@ -177,6 +177,30 @@ def test_scale_clamp_and_eps():
     _fwd_bwd(case, "scale_clamp_eps")
 
 
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("q_offset", [0, 1, 3])
+def test_codes_only_forward(dtype, q_offset):
+    """y = NULL: only the packed int8 codes (and the scales) are written; q at any byte offset."""
+    rng = np.random.default_rng(40 + q_offset)
+    outer, c, inner = 2, 6, 5003
+    x = (rng.standard_normal((outer, c, inner)) * 2).astype(dtype)
+    case = workloads.TensorCase("codes", x.shape, outer, c, inner, -128, 127, x,
+                                workloads.theta_for_scale(rng.uniform(0.01, 0.03, c)))
+    H.say("codes only %s q_offset=%d" % (np.dtype(dtype).name, q_offset))
+    s_ref, _, _, q_ref = H.oracle_forward(case)
+    n = case.numel
+    xd, theta = H.dev(x.reshape(-1)), H.dev(case.theta)
+    qbuf = torch.full((n + 16,), 99, dtype=torch.int8, device="cuda")
+    qv = qbuf[q_offset:q_offset + n]
+    s = torch.empty(c, device="cuda")
+    d = fq.FqTensor.from_torch(outer, c, inner, -128, 127, x=xd, q=qv, theta=theta, s=s)
+    fq.fq_forward(d)
+    torch.cuda.synchronize()
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+    assert np.array_equal(qv.cpu().numpy().astype(np.int32), q_ref)
+    assert torch.all(qbuf[:q_offset] == 99) and torch.all(qbuf[q_offset + n:] == 99)
+
+
 def test_scale_sweep_bit_exact():
     """Eq. (3)-(4) over two million theta values (dense sweep, random, specials), through the
     scale-only path of a tensor with channels but no elements."""
