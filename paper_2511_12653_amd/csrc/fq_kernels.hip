@@ -140,22 +140,39 @@ __device__ __forceinline__ Scale compute_scale(float theta, float eps, float s_m
 struct QParams {
     double rd;      // RN64(1 / s)
     float s, lo, hi;
+    int ilo, ihi;   // the same bounds as integers (for the int8 codes)
 };
 
 __device__ __forceinline__ float quotient(float x, const QParams &p) { return (float)((double)x * p.rd); }
 
-// forward value; qf receives the integer-valued code (NaN for a NaN quotient)
-__device__ __forceinline__ float fq_value(float x, const QParams &p, float &qf)
+// forward value y = s * round(clip(v)); a NaN quotient gives NaN
+__device__ __forceinline__ float fq_value(float v, const QParams &p)
 {
-    float v = quotient(x, p);
     float q = __builtin_rintf(__builtin_amdgcn_fmed3f(v, p.lo, p.hi));
     float y = q * p.s;
-    bool is_nan = v != v;
-    qf = is_nan ? v : q;
-    return is_nan ? v : y;
+    return v != v ? v : y;
 }
 
-__device__ __forceinline__ int8_t code_of(float qf) { return qf != qf ? (int8_t)0 : (int8_t)(int)qf; }
+// integer code clip(round(v)) (the same as round(clip(v)) for integer bounds), 0 for a NaN
+// quotient.  v_cvt_i32_f32 itself maps NaN to 0 and saturates +-Inf and huge values, so no
+// select is needed; it is written as an instruction because the C conversion of NaN/Inf is
+// undefined.
+__device__ __forceinline__ int fq_code(float v, const QParams &p)
+{
+    int c;
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(c) : "v"(__builtin_rintf(v)));
+    c = c < p.ilo ? p.ilo : c;
+    c = c > p.ihi ? p.ihi : c;
+    return c;
+}
+
+// low bytes of four ints -> one dword (v_perm_b32 twice + or)
+__device__ __forceinline__ unsigned pack_codes4(int c0, int c1, int c2, int c3)
+{
+    const unsigned lo = __builtin_amdgcn_perm((unsigned)c1, (unsigned)c0, 0x0c0c0400u);
+    const unsigned hi = __builtin_amdgcn_perm((unsigned)c3, (unsigned)c2, 0x04000c0cu);
+    return lo | hi;
+}
 
 // backward: returns t = dy/ds and whether the quotient is inside [lo, hi] (inclusive).
 // in range: t = rint(v) - v;  below: lo;  above: hi;  NaN quotient: out of range, t = NaN.
@@ -290,44 +307,42 @@ __device__ __forceinline__ QParams block_params(const DevTensor &d, float theta,
     p.s = bs.s;
     p.lo = d.lo;
     p.hi = d.hi;
+    p.ilo = (int)d.lo;
+    p.ihi = (int)d.hi;
     return p;
 }
 
 // ---------------------------------------------------------------------------------------------
 // Forward.
-template <typename T, bool EMIT_Q>
+template <typename T, bool WRITE_Y, bool EMIT_Q>
 __device__ __forceinline__ void forward_elem(const T *x, T *y, int8_t *q, int i, const QParams &p)
 {
-    float qf;
-    float yf = fq_value((float)ld_global(x + i), p, qf);
-    if (y) st_global(y + i, (T)yf);
-    if (EMIT_Q && q) st_global(q + i, code_of(qf));
+    const float v = quotient((float)ld_global(x + i), p);
+    if (WRITE_Y) st_global(y + i, (T)fq_value(v, p));
+    if (EMIT_Q) st_global(q + i, (int8_t)fq_code(v, p));
 }
 
-// N int8 codes of one vector, packed: one 64-bit (FP16 input) or 32-bit (FP32 input) store.
-template <int N> struct CodeVec;
-template <> struct CodeVec<8> { typedef signed char type __attribute__((ext_vector_type(8))); };
-template <> struct CodeVec<4> { typedef signed char type __attribute__((ext_vector_type(4))); };
-
-template <typename T, bool EMIT_Q>
+// WRITE_Y: write the dequantized tensor y.  EMIT_Q: write the int8 codes, N per lane packed into
+// one 64-bit (FP16 input) or 32-bit (FP32 input) store.  At least one of the two.
+template <typename T, bool WRITE_Y, bool EMIT_Q>
 __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local_block)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
-    typedef typename CodeVec<N>::type QV;
+    typedef unsigned QV __attribute__((ext_vector_type(N / 4)));
     const Chunk ck = locate_chunk(d, local_block);
     const T *x = (const T *)d.x + ck.first;
-    T *y = d.y ? (T *)d.y + ck.first : nullptr;          // NULL: integer codes only
-    int8_t *q = (EMIT_Q && d.q) ? d.q + ck.first : nullptr;
+    T *y = WRITE_Y ? (T *)d.y + ck.first : nullptr;
+    int8_t *q = EMIT_Q ? d.q + ck.first : nullptr;
     const int tid = threadIdx.x;
     const float theta = ld_uniform(d.theta + ck.channel);
 
-    const bool vector_ok = !y || (((uintptr_t)x ^ (uintptr_t)y) & (kVecBytes - 1)) == 0;
+    const bool vector_ok = !WRITE_Y || (((uintptr_t)x ^ (uintptr_t)y) & (kVecBytes - 1)) == 0;
     const int head = vector_ok ? head_elems<T>(x, ck.n) : ck.n;
     const int nvec = (ck.n - head) / N;
     const VT *xv = (const VT *)(x + head);
-    VT *yv = y ? (VT *)(y + head) : nullptr;
-    const bool q_packed = EMIT_Q && q && ((uintptr_t)(q + head) % N) == 0;
+    VT *yv = WRITE_Y ? (VT *)(y + head) : nullptr;
+    const bool q_packed = EMIT_Q && ((uintptr_t)(q + head) % N) == 0;
 
     // Issue the first row of loads (straight-line: out-of-range lanes re-read the last vector)
     // before the long binary64 scale evaluation, which then runs under the memory latency.
@@ -350,20 +365,28 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
         for (int u = 0; u < kUnroll; ++u) {
             int v = v0 + u * kBlock + tid;
             if (v < nvec) {
-                VT o;
-                float qf[N];
+                float quot[N];
 #pragma unroll
-                for (int e = 0; e < N; ++e) o[e] = (T)fq_value((float)r[u][e], p, qf[e]);
-                if (y) st_stream(yv + v, o);
-                if (EMIT_Q && q) {
-                    QV codes;
+                for (int e = 0; e < N; ++e) quot[e] = quotient((float)r[u][e], p);
+                if (WRITE_Y) {
+                    VT o;
 #pragma unroll
-                    for (int e = 0; e < N; ++e) codes[e] = code_of(qf[e]);
+                    for (int e = 0; e < N; ++e) o[e] = (T)fq_value(quot[e], p);
+                    st_stream(yv + v, o);
+                }
+                if (EMIT_Q) {
+                    int c[N];
+#pragma unroll
+                    for (int e = 0; e < N; ++e) c[e] = fq_code(quot[e], p);
                     if (q_packed) {
+                        QV codes;
+#pragma unroll
+                        for (int g = 0; g < N / 4; ++g)
+                            codes[g] = pack_codes4(c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]);
                         st_stream((QV *)(q + head + v * N), codes);
                     } else {
 #pragma unroll
-                        for (int e = 0; e < N; ++e) st_global(q + head + v * N + e, (int8_t)codes[e]);
+                        for (int e = 0; e < N; ++e) st_global(q + head + v * N + e, (int8_t)c[e]);
                     }
                 }
             }
@@ -380,8 +403,17 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
 
     // scalar head (before the first 16-byte boundary, or the whole chunk if x and y are
     // misaligned relative to each other) and tail (after the last whole vector)
-    for (int i = tid; i < head; i += kBlock) forward_elem<T, EMIT_Q>(x, y, q, i, p);
-    for (int i = head + nvec * N + tid; i < ck.n; i += kBlock) forward_elem<T, EMIT_Q>(x, y, q, i, p);
+    for (int i = tid; i < head; i += kBlock) forward_elem<T, WRITE_Y, EMIT_Q>(x, y, q, i, p);
+    for (int i = head + nvec * N + tid; i < ck.n; i += kBlock) forward_elem<T, WRITE_Y, EMIT_Q>(x, y, q, i, p);
+}
+
+// what one tensor asks of the forward pass: y only, y and codes, or codes only
+template <typename T>
+__device__ __forceinline__ void forward_dispatch(const DevTensor &d, unsigned local_block)
+{
+    if (!d.q) forward_chunk<T, true, false>(d, local_block);
+    else if (d.y) forward_chunk<T, true, true>(d, local_block);
+    else forward_chunk<T, false, true>(d, local_block);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -620,19 +652,25 @@ __device__ __forceinline__ DevTensor fetch(const DevTensor *table, int i)
 }
 
 // Single tensor: descriptor in the kernel arguments (SGPRs), dtype fixed at compile time.
-template <typename T, bool EMIT_Q>
+template <typename T, bool WRITE_Y, bool EMIT_Q>
 __global__ void __launch_bounds__(kBlock) forward_kernel(const DevTensor d)
 {
-    forward_chunk<T, EMIT_Q>(d, blockIdx.x);
+    forward_chunk<T, WRITE_Y, EMIT_Q>(d, blockIdx.x);
 }
 
-template <bool EMIT_Q>
+// ANY_Q = false: no tensor of the list wants codes (the usual case; keeps the kernel lean)
+template <bool ANY_Q>
 __global__ void __launch_bounds__(kBlock) forward_multi_kernel(const DevTensor *table, int n)
 {
     const DevTensor d = fetch(table, find_by_block((const FQ_CONST DevTensor *)table, n, blockIdx.x));
     const unsigned local = blockIdx.x - d.block_begin;
-    if (d.dtype == 0) forward_chunk<_Float16, EMIT_Q>(d, local);
-    else forward_chunk<float, EMIT_Q>(d, local);
+    if (ANY_Q) {
+        if (d.dtype == 0) forward_dispatch<_Float16>(d, local);
+        else forward_dispatch<float>(d, local);
+    } else {
+        if (d.dtype == 0) forward_chunk<_Float16, true, false>(d, local);
+        else forward_chunk<float, true, false>(d, local);
+    }
 }
 
 template <typename T, bool FUSED>
@@ -690,6 +728,14 @@ static void launch(K kernel, unsigned blocks, hipStream_t st, Args... args)
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kBlock), 0, st, args...);
 }
 
+template <typename T>
+static void launch_forward_single(const DevTensor &d, unsigned blocks, hipStream_t st)
+{
+    if (!d.q) launch(forward_kernel<T, true, false>, blocks, st, d);
+    else if (d.y) launch(forward_kernel<T, true, true>, blocks, st, d);
+    else launch(forward_kernel<T, false, true>, blocks, st, d);
+}
+
 int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
@@ -697,11 +743,9 @@ int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream)
         if (emit_q) launch(forward_multi_kernel<true>, blocks, st, a.table, a.n);
         else launch(forward_multi_kernel<false>, blocks, st, a.table, a.n);
     } else if (a.one.dtype == 0) {
-        if (emit_q) launch(forward_kernel<_Float16, true>, blocks, st, a.one);
-        else launch(forward_kernel<_Float16, false>, blocks, st, a.one);
+        launch_forward_single<_Float16>(a.one, blocks, st);
     } else {
-        if (emit_q) launch(forward_kernel<float, true>, blocks, st, a.one);
-        else launch(forward_kernel<float, false>, blocks, st, a.one);
+        launch_forward_single<float>(a.one, blocks, st);
     }
     return (int)hipGetLastError();
 }
