@@ -48,7 +48,8 @@ typedef enum fq_status {
     FQ_ERR_WORKSPACE = -6,     /* workspace NULL or smaller than fq_workspace_bytes() */
     FQ_ERR_SCALE_PARAMS = -7,  /* need finite eps, 0 < s_min <= s_max, no NaN */
     FQ_ERR_LAUNCH = -8,        /* the HIP runtime reported an error while enqueuing */
-    FQ_ERR_ALIAS = -9          /* output partially overlaps its input (exact in-place is allowed) */
+    FQ_ERR_ALIAS = -9,         /* output partially overlaps its input (exact in-place is allowed) */
+    FQ_ERR_OPTIMIZER = -10     /* bad fq_adam: step < 1, beta outside [0,1), lr/eps not finite or eps < 0 */
 } fq_status;
 
 typedef enum fq_dtype { FQ_F16 = 0, FQ_F32 = 1 } fq_dtype;
@@ -63,6 +64,24 @@ enum {
 };
 
 enum { FQ_MODE_FORWARD = 1, FQ_MODE_BACKWARD = 2 };
+
+/*
+ * Optional: one Adam step on theta, fused into the end of the backward pass (the paper trains
+ * only the scale parameters, with Adam: Sec. 3.2 "Training details"; it prints no
+ * hyper-parameters, so they are fields).  Kingma & Ba (2015), Algorithm 1, in binary32:
+ *   m <- beta1*m + (1-beta1)*g;  v <- beta2*v + ((1-beta2)*g)*g;
+ *   theta_out <- theta - (lr*(m/(1-beta1^step))) / (sqrt(v/(1-beta2^step)) + eps),   g = gtheta.
+ * The constants are evaluated in binary64 on the host and rounded to binary32 once each.  A
+ * channel whose gradient is not finite keeps m, v and theta (the "isfinite guard" of Sec. 4.1.5).
+ * Host struct; m, v, theta_out are device pointers to [channels] floats owned by the caller.
+ * theta_out may be the tensor's theta itself (in place) or another buffer.
+ */
+typedef struct fq_adam {
+    double lr, beta1, beta2, eps;     /* lr finite, 0 <= beta < 1, eps >= 0 */
+    int64_t step;                     /* t >= 1: this is the t-th update */
+    float *m, *v;                     /* in/out: first and second moment estimates */
+    float *theta_out;                 /* out: updated parameters */
+} fq_adam;
 
 /* One tensor to fake-quantize.  Host struct; the pointers inside are device pointers. */
 typedef struct fq_tensor {
@@ -81,6 +100,7 @@ typedef struct fq_tensor {
     void *gx;                         /* out (backward); may be exactly gy; unused with FQ_FLAG_NO_DX */
     float *gs;                        /* out [channels], optional: dL/ds (overwritten) */
     float *gtheta;                    /* out [channels], optional: dL/dtheta (overwritten) */
+    const fq_adam *adam;              /* host pointer, optional (backward): fused Adam step on theta */
 } fq_tensor;
 
 /*
@@ -145,7 +165,9 @@ fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode,
  * workspace must stay allocated at the same addresses, the workspace must not be written by
  * anything else (one workspace per plan; zero it before fq_plan_create for backward plans), and
  * fq_plan_run must be ordered after fq_plan_create's stream work.  Tensor contents and theta may
- * change freely between runs.  fq_plan_destroy frees the host-side plan only (NULL is allowed).
+ * change freely between runs.  Descriptors with a fused Adam step are refused
+ * (FQ_ERR_OPTIMIZER): its bias corrections change with every step, use fq_multi_tensor for
+ * those.  fq_plan_destroy frees the host-side plan only (NULL is allowed).
  */
 typedef struct fq_plan fq_plan;
 fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,

@@ -245,3 +245,35 @@ void fqo_backward(const void *x, const void *gy, int dtype,
         }
     }
 }
+
+/* ---- one Adam step on the scale parameters -------------------------------- */
+/*
+ * The paper trains only the scale parameters, with Adam (Sec. 3.2 "Training details"); it
+ * prints no hyper-parameters, so they are arguments.  Kingma & Ba (2015), Algorithm 1, in
+ * binary32, every operation rounded on its own, in the order written:
+ *   m     <- beta1*m + (1-beta1)*g
+ *   v     <- beta2*v + ((1-beta2)*g)*g
+ *   theta <- theta - (lr * (m/bc1)) / (sqrt(v/bc2) + eps)
+ * The six constants beta1, 1-beta1, beta2, 1-beta2, bc1 = 1-beta1^t, bc2 = 1-beta2^t are
+ * evaluated by the caller from binary64 hyper-parameters and rounded to binary32 once each
+ * (1-beta2 formed in binary32 from a binary32 beta2 would be off by 1e-5 relative).
+ * A channel whose gradient is not finite is left untouched (m, v, theta keep their values):
+ * the "isfinite guard" of Sec. 4.1.5.
+ */
+void fqo_adam(const float *g, int64_t C, float lr, float beta1, float one_minus_beta1, float beta2,
+              float one_minus_beta2, float eps, float bc1, float bc2,
+              float *m, float *v, const float *theta_in, float *theta_out)
+{
+    for (int64_t c = 0; c < C; ++c) {
+        if (!isfinite(g[c])) {
+            theta_out[c] = theta_in[c];
+            continue;
+        }
+        float mm = beta1 * m[c] + one_minus_beta1 * g[c];
+        float vv = beta2 * v[c] + (one_minus_beta2 * g[c]) * g[c];
+        float mhat = mm / bc1, vhat = vv / bc2;
+        m[c] = mm;
+        v[c] = vv;
+        theta_out[c] = theta_in[c] - (lr * mhat) / (sqrtf(vhat) + eps);
+    }
+}

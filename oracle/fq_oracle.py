@@ -38,6 +38,8 @@ def lib():
         L.fqo_backward.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, i32, i32,
                                    vp, vp, vp, vp, vp]
         L.fqo_backward.restype = None
+        L.fqo_adam.argtypes = [vp, i64, f32, f32, f32, f32, f32, f32, f32, f32, vp, vp, vp, vp]
+        L.fqo_adam.restype = None
         _LIB = L
     return _LIB
 
@@ -104,3 +106,23 @@ def backward(x, gy, s, theta, clip_active, qmin, qmax, outer, channels, inner, w
     lib().fqo_backward(_p(x), _p(gy), _DT[x.dtype], outer, channels, inner, _p(s), _p(theta),
                        _p(clip_active), qmin, qmax, _p(gx), _p(acc), _p(aabs), _p(gs), _p(gtheta))
     return dict(gx=gx, gs=gs, gtheta=gtheta, acc=acc, aabs=aabs)
+
+
+def adam_constants(lr, beta1, beta2, eps, step):
+    """The eight float32 constants of one Adam step, each evaluated in float64 and rounded once:
+    lr, beta1, 1-beta1, beta2, 1-beta2, eps, 1-beta1^t, 1-beta2^t."""
+    f = lambda x: float(np.float32(x))
+    return (f(lr), f(beta1), f(1.0 - beta1), f(beta2), f(1.0 - beta2), f(eps),
+            f(1.0 - beta1 ** step), f(1.0 - beta2 ** step))
+
+
+def adam(g, m, v, theta, lr, beta1, beta2, eps, step):
+    """One Adam step (Kingma & Ba Alg. 1, float32).  Returns (theta_new, m_new, v_new)."""
+    g = np.ascontiguousarray(g, dtype=np.float32).reshape(-1)
+    m = np.array(m, dtype=np.float32).reshape(-1).copy()
+    v = np.array(v, dtype=np.float32).reshape(-1).copy()
+    theta = np.ascontiguousarray(theta, dtype=np.float32).reshape(-1)
+    out = np.empty_like(theta)
+    lr_, b1, omb1, b2, omb2, eps_, bc1, bc2 = adam_constants(lr, beta1, beta2, eps, step)
+    lib().fqo_adam(_p(g), g.size, lr_, b1, omb1, b2, omb2, eps_, bc1, bc2, _p(m), _p(v), _p(theta), _p(out))
+    return out, m, v

@@ -33,6 +33,21 @@ def _load():
     return ctypes.CDLL(_LIB_PATH)
 
 
+class FqAdam(ctypes.Structure):
+    """Mirror of `struct fq_adam` (host struct; m, v, theta_out are device pointers)."""
+    _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("step", ctypes.c_int64),
+                ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("theta_out", ctypes.c_void_p)]
+
+    @classmethod
+    def from_torch(cls, m, v, theta_out, lr, beta1=0.9, beta2=0.999, eps=1e-8, step=1):
+        import torch
+        for t in (m, v, theta_out):
+            if t.dtype != torch.float32 or not t.is_contiguous():
+                raise TypeError("Adam state must be contiguous float32")
+        return cls(lr, beta1, beta2, eps, step, m.data_ptr(), v.data_ptr(), theta_out.data_ptr())
+
+
 class FqTensor(ctypes.Structure):
     """Mirror of `struct fq_tensor` (host struct holding device pointers)."""
     _fields_ = [
@@ -44,12 +59,19 @@ class FqTensor(ctypes.Structure):
         ("theta", ctypes.c_void_p), ("s", ctypes.c_void_p),
         ("gy", ctypes.c_void_p), ("gx", ctypes.c_void_p),
         ("gs", ctypes.c_void_p), ("gtheta", ctypes.c_void_p),
+        ("adam", ctypes.POINTER(FqAdam)),
     ]
+
+    def set_adam(self, adam):
+        """Attach (or with None detach) a fused Adam step; keeps the FqAdam object alive."""
+        self._adam_ref = adam
+        self.adam = ctypes.pointer(adam) if adam is not None else ctypes.POINTER(FqAdam)()
+        return self
 
     @classmethod
     def from_torch(cls, outer, channels, inner, qmin, qmax, x=None, y=None, q=None, theta=None,
                    s=None, gy=None, gx=None, gs=None, gtheta=None, eps=0.0, s_min=FLT_MIN,
-                   s_max=float("inf"), flags=0, dtype=None):
+                   s_max=float("inf"), flags=0, dtype=None, adam=None):
         """Marshal torch tensors (device memory owned by the caller) into a descriptor."""
         import torch
 
@@ -75,10 +97,13 @@ class FqTensor(ctypes.Structure):
         for t in (theta, s, gs, gtheta):
             if t is not None and t.numel() != channels:
                 raise ValueError("per-channel tensor has %d elements, want %d" % (t.numel(), channels))
-        return cls(outer, channels, inner, dtype, qmin, qmax, eps, s_min, s_max, flags,
-                   ptr(x, tdt), ptr(y, tdt), ptr(q, torch.int8), ptr(theta, torch.float32),
-                   ptr(s, torch.float32), ptr(gy, tdt), ptr(gx, tdt), ptr(gs, torch.float32),
-                   ptr(gtheta, torch.float32))
+        t = cls(outer, channels, inner, dtype, qmin, qmax, eps, s_min, s_max, flags,
+                ptr(x, tdt), ptr(y, tdt), ptr(q, torch.int8), ptr(theta, torch.float32),
+                ptr(s, torch.float32), ptr(gy, tdt), ptr(gx, tdt), ptr(gs, torch.float32),
+                ptr(gtheta, torch.float32))
+        if adam is not None:
+            t.set_adam(adam)
+        return t
 
 
 class FqError(RuntimeError):

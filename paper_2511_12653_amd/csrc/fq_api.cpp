@@ -109,6 +109,14 @@ fq_status validate_one(const fq_tensor &t, int mode, Plan &p)
         if (!aligned(t.gy, esz) || (need_gx && !aligned(t.gx, esz))) return FQ_ERR_ALIGN;
         if (need_gx && (partial_overlap(t.gy, t.gx, bytes) || partial_overlap(t.x, t.gx, bytes)))
             return FQ_ERR_ALIAS;
+        if (t.adam) {
+            const fq_adam &a = *t.adam;
+            if (a.step < 1 || !(a.beta1 >= 0.0 && a.beta1 < 1.0) || !(a.beta2 >= 0.0 && a.beta2 < 1.0) ||
+                !std::isfinite(a.lr) || !std::isfinite(a.eps) || a.eps < 0.0)
+                return FQ_ERR_OPTIMIZER;
+            if (t.channels > 0 && (!a.m || !a.v || !a.theta_out)) return FQ_ERR_NULL;
+            if (!aligned(a.m, 4) || !aligned(a.v, 4) || !aligned(a.theta_out, 4)) return FQ_ERR_ALIGN;
+        }
     }
     return FQ_OK;
 }
@@ -176,6 +184,16 @@ void build_table(const fq_tensor *ts, int n, const Layout &L, char *workspace, s
         d.hi = (float)t.qmax;
         d.eps = t.eps; d.s_min = t.s_min; d.s_max = t.s_max;
         d.flags = t.flags;
+        if (t.adam && t.channels > 0) {
+            const fq_adam &a = *t.adam;
+            d.adam_m = a.m; d.adam_v = a.v; d.adam_theta_out = a.theta_out;
+            d.adam_lr = (float)a.lr;
+            d.adam_beta1 = (float)a.beta1; d.adam_one_minus_beta1 = (float)(1.0 - a.beta1);
+            d.adam_beta2 = (float)a.beta2; d.adam_one_minus_beta2 = (float)(1.0 - a.beta2);
+            d.adam_eps = (float)a.eps;
+            d.adam_bc1 = (float)(1.0 - std::pow(a.beta1, (double)a.step));
+            d.adam_bc2 = (float)(1.0 - std::pow(a.beta2, (double)a.step));
+        }
         block += p.blocks;
         chan += t.channels;
     }
@@ -364,6 +382,9 @@ fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, 
 {
     if (!plan) return FQ_ERR_NULL;
     *plan = nullptr;
+    // a plan freezes its descriptors, and Adam's bias corrections change with every step
+    for (int i = 0; ts && i < n; ++i)
+        if (ts[i].adam) return FQ_ERR_OPTIMIZER;
     fq_plan *p = new (std::nothrow) fq_plan();
     if (!p) return FQ_ERR_LAUNCH;
     fq_status st = fq::prepare(ts, n, mode, true, workspace, ws_bytes, hip_stream, p->prepared);
@@ -396,6 +417,7 @@ const char *fq_status_string(fq_status status)
     case FQ_ERR_SCALE_PARAMS: return "bad eps / s_min / s_max";
     case FQ_ERR_LAUNCH: return "HIP runtime error while enqueuing";
     case FQ_ERR_ALIAS: return "output partially overlaps an input";
+    case FQ_ERR_OPTIMIZER: return "bad Adam parameters";
     }
     return "unknown status";
 }

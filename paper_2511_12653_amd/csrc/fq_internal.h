@@ -37,6 +37,10 @@ struct DevTensor {
     float lo, hi;              // (float)qmin, (float)qmax
     float eps, s_min, s_max;
     unsigned flags;
+    // fused Adam step on theta (backward); adam_m == nullptr: none
+    float *adam_m, *adam_v, *adam_theta_out;
+    float adam_lr, adam_beta1, adam_one_minus_beta1, adam_beta2, adam_one_minus_beta2, adam_eps;
+    float adam_bc1, adam_bc2;      // 1 - beta1^t, 1 - beta2^t
 };
 
 struct KArgs {

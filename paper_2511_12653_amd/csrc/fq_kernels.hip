@@ -514,9 +514,27 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
 // Chain rule through Eq. (3)-(4) and the per-channel outputs of the backward pass.
 __device__ __forceinline__ void write_channel_grads(const DevTensor &d, unsigned c, double total, const BlockScale &bs)
 {
+    const float g = bs.clip_active ? 0.0f : (float)(total * bs.sigmoid);
     if (d.gs) st_global(d.gs + c, (float)total);
-    if (d.gtheta) st_global(d.gtheta + c, bs.clip_active ? 0.0f : (float)(total * bs.sigmoid));
+    if (d.gtheta) st_global(d.gtheta + c, g);
     if (d.s) st_global(d.s + c, bs.s);
+    if (d.adam_m) {
+        // One Adam step on theta_c (Kingma & Ba, Algorithm 1), binary32, each operation rounded
+        // on its own.  Every block of this channel has finished reading theta_c by now (this
+        // code runs after all of them have handed in their sums), so theta may be updated in
+        // place.  A non-finite gradient leaves m, v and theta as they are.
+        const float theta = ld_global(d.theta + c);
+        float out = theta;
+        if (__builtin_isfinite(g)) {
+            const float m = d.adam_beta1 * ld_global(d.adam_m + c) + d.adam_one_minus_beta1 * g;
+            const float v = d.adam_beta2 * ld_global(d.adam_v + c) + (d.adam_one_minus_beta2 * g) * g;
+            const float mhat = m / d.adam_bc1, vhat = v / d.adam_bc2;
+            st_global(d.adam_m + c, m);
+            st_global(d.adam_v + c, v);
+            out = theta - (d.adam_lr * mhat) / (__builtin_sqrtf(vhat) + d.adam_eps);
+        }
+        st_global(d.adam_theta_out + c, out);
+    }
 }
 
 // Sum the per-block partials of channel c in a fixed order (thread-strided binary64 sums, fixed

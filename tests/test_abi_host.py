@@ -32,7 +32,8 @@ def test_exports_every_declared_symbol(fq):
 
 def test_struct_size_matches_header(fq):
     # 3*8 + 3*4 + 3*4 + 4 (flags) = 52 -> padded to 56, then 9 pointers
-    assert ctypes.sizeof(fq.FqTensor) == 56 + 9 * 8
+    assert ctypes.sizeof(fq.FqTensor) == 56 + 10 * 8
+    assert ctypes.sizeof(fq.FqAdam) == 4 * 8 + 8 + 3 * 8
 
 
 def _desc(fq, **kw):
@@ -47,7 +48,7 @@ def test_validate_ok_and_status_strings(fq):
     assert fq.fq_validate(_desc(fq), fq.FQ_MODE_FORWARD) == 0
     assert fq.fq_validate(_desc(fq), fq.FQ_MODE_BACKWARD) == 0
     assert fq.fq_status_string(0) == "ok"
-    for code in range(-9, 0):
+    for code in range(-10, 0):
         assert fq.fq_status_string(code) not in ("ok", "unknown status")
     assert fq.fq_status_string(-99) == "unknown status"
 
@@ -84,6 +85,19 @@ def test_validate_accepts_edge_cases(fq):
     # bad mode / list errors
     assert fq.fq_validate(_desc(fq), 3) == -3
     assert fq.fq_validate([_desc(fq), _desc(fq, dtype=9)], 1) == -2
+
+
+def test_validate_adam(fq):
+    def with_adam(**kw):
+        a = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, step=1, m=0x80000, v=0x90000, theta_out=0x30000)
+        a.update(kw)
+        return _desc(fq).set_adam(fq.FqAdam(**a))
+    assert fq.fq_validate(with_adam(), 2) == 0
+    assert fq.fq_validate(with_adam(), 1) == 0                       # ignored by the forward pass
+    for kw in (dict(step=0), dict(beta1=1.0), dict(beta2=-0.1), dict(lr=float("inf")), dict(eps=-1.0)):
+        assert fq.fq_validate(with_adam(**kw), 2) == -10
+    assert fq.fq_validate(with_adam(m=None), 2) == -1
+    assert fq.fq_validate(with_adam(v=0x90002), 2) == -5
 
 
 def test_workspace_bytes(fq):
