@@ -2,11 +2,11 @@
 // and the straight-through backward stated next to Eq. (5)).
 //
 // The work is HBM-bound elementwise traffic plus one per-channel reduction, so there is no MFMA
-// here.  Each 256-thread block owns one chunk (at most 16 KiB of input) that lies inside a single
+// here.  Each 256-thread block owns one chunk (at most 20 KiB of input) that lies inside a single
 // [outer, channel] slab, so the scale is uniform over the block; lanes move 128-bit vectors
-// (global_load/store_dwordx4), FP16 is widened/narrowed in registers.  Backward adds a DPP
-// wavefront reduction, an LDS block reduction, one partial sum per block, and a fixed-order final
-// sum per channel carried out by whichever block of that channel finishes last.
+// (global_load/store_dwordx4, non-temporal), FP16 is widened/narrowed in registers.  Backward adds
+// a DPP wavefront reduction, an LDS block reduction and a fixed-order combination of the blocks
+// of a channel (direct, by atomic exchange, or by ticket: see backward_block); no float atomics.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -32,15 +32,13 @@ static_assert(kChunkVecs % kBlock == 0, "chunk must be a whole number of block-w
 // ---------------------------------------------------------------------------------------------
 // Eq. (3)-(4): s = clip(softplus(theta) + eps, s_min, s_max).  Evaluated in binary64 and rounded
 // to binary32 once, so the value does not depend on the accuracy of a binary32 exp/log.
-// clip_active: the clamp changed the value (its derivative is then zero).
 struct Scale {
     float s;             // Eq. (3)-(4)
     bool clip_active;    // the clamp changed the value (its derivative is then zero)
     double sigmoid;      // d softplus / d theta
 };
 
-// What a block needs of its channel's scale, evaluated once by wavefront 0 (the binary64
-// softplus is a couple of hundred instructions) and handed to the others through LDS.
+// What a block needs of its channel's scale (see block_params).
 struct BlockScale {
     double rd;           // RN64(1 / s)
     double sigmoid;
