@@ -542,11 +542,23 @@ __device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c,
 {
     const unsigned bpc = d.outer * d.cps;
     double acc = 0.0;
-    for (unsigned j = threadIdx.x; j < bpc; j += kBlock) {
-        unsigned o = j / d.cps;
-        unsigned k = j - o * d.cps;
-        size_t idx = ((size_t)o * d.channels + c) * d.cps + k;
-        acc += __hip_atomic_load(&d.partial[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // thread t adds sums t, t+256, t+512, ... in that order; eight loads are kept in flight
+    constexpr unsigned kBatch = 8;
+    for (unsigned j0 = threadIdx.x; j0 < bpc; j0 += kBlock * kBatch) {
+        double part[kBatch];
+#pragma unroll
+        for (unsigned i = 0; i < kBatch; ++i) {
+            const unsigned j = j0 + i * kBlock;
+            part[i] = 0.0;
+            if (j < bpc) {
+                const unsigned o = j / d.cps;
+                const unsigned k = j - o * d.cps;
+                const size_t idx = ((size_t)o * d.channels + c) * d.cps + k;
+                part[i] = __hip_atomic_load(&d.partial[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+#pragma unroll
+        for (unsigned i = 0; i < kBatch; ++i) acc += part[i];
     }
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = acc;
