@@ -185,26 +185,28 @@ __device__ __forceinline__ float ste_terms(float x, const QParams &p, bool &in_r
 }
 
 // ---------------------------------------------------------------------------------------------
-// Reductions.  DPP inside rows of 16 lanes (a binary64 value moves as its two 32-bit halves),
-// cross-row exchange for the last two steps; every lane ends with the same sum and the order of
-// additions is fixed.
-template <int CTRL> __device__ __forceinline__ double dpp_move(double v)
+// Reductions, all in DPP (a binary64 value moves as its two 32-bit halves): butterflies inside
+// rows of 16 lanes, then row_bcast15 / row_bcast31 carry the row sums across rows.  The sum of
+// the whole wavefront ends in lanes 48..63 (kSumLane reads it); the order of additions is fixed.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ double dpp_move(double v)
 {
     typedef int i32x2 __attribute__((ext_vector_type(2)));
     i32x2 w = __builtin_bit_cast(i32x2, v);
-    w[0] = __builtin_amdgcn_update_dpp(0, w[0], CTRL, 0xf, 0xf, false);
-    w[1] = __builtin_amdgcn_update_dpp(0, w[1], CTRL, 0xf, 0xf, false);
+    w[0] = __builtin_amdgcn_update_dpp(0, w[0], CTRL, ROW_MASK, 0xf, false);   // masked rows get 0
+    w[1] = __builtin_amdgcn_update_dpp(0, w[1], CTRL, ROW_MASK, 0xf, false);
     return __builtin_bit_cast(double, w);
 }
 
+constexpr int kSumLane = 63;
+
 __device__ __forceinline__ double wave_sum(double v)
 {
-    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
-    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
-    v += dpp_move<0x141>(v);   // row_half_mirror
-    v += dpp_move<0x140>(v);   // row_mirror
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
+    v += dpp_move<0xB1, 0xf>(v);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E, 0xf>(v);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141, 0xf>(v);   // row_half_mirror
+    v += dpp_move<0x140, 0xf>(v);   // row_mirror: every lane now holds its row's sum
+    v += dpp_move<0x142, 0xa>(v);   // row_bcast15: rows 1 and 3 add the row before them
+    v += dpp_move<0x143, 0xc>(v);   // row_bcast31: rows 2 and 3 add rows 0+1
     return v;
 }
 
@@ -561,7 +563,7 @@ __device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c,
         for (unsigned i = 0; i < kBatch; ++i) acc += part[i];
     }
     acc = wave_sum(acc);
-    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = acc;
+    if ((threadIdx.x & 63) == kSumLane) lds[threadIdx.x >> 6] = acc;
     __syncthreads();
     if (threadIdx.x == 0) {
         double total = 0.0;
@@ -598,7 +600,7 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
     double sum = write_gx ? backward_chunk<T, true>(d, ck, bs) : backward_chunk<T, false>(d, ck, bs);
 
     sum = wave_sum(sum);
-    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = sum;
+    if ((threadIdx.x & 63) == kSumLane) wave_part[threadIdx.x >> 6] = sum;
     __syncthreads();
     const unsigned bpc = d.outer * d.cps;
     if (threadIdx.x == 0) {
