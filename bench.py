@@ -246,6 +246,37 @@ def main():
                         "bracket_two_us": round(t_two * 1e6, 2), "bracket_one_us": round(t_one * 1e6, 2),
                         "samples": [len(dur[2]), len(dur[1])]}
 
+    # ---- context: what plain library streaming kernels reach on the same buffers ---------------
+    # (outside the timed region; single-tensor training workloads only).  torch's device copy moves
+    # the forward's bytes (read b, write b per element), torch.add the backward's (read 2b, write
+    # b): neither does any of the quantizer's arithmetic, so their time per launch is the
+    # streaming floor of this machine for that traffic, launched back to back over the same ring.
+    floors = None
+    if train and not multi and not args.no_kernel_events:
+        def train_of(fn, reps=10 * ring):
+            a, z = new_event(), new_event()
+            for i in range(ring):
+                fn(i)
+            torch.cuda.synchronize()
+            hip.hipEventRecord(a, sp)
+            for i in range(reps):
+                fn(i % ring)
+            hip.hipEventRecord(z, sp)
+            torch.cuda.synchronize()
+            ms = ctypes.c_float()
+            hip.hipEventElapsedTime(ctypes.byref(ms), a, z)
+            return ms.value / reps * 1e3
+
+        per_set = len(cases)
+        t_copy = train_of(lambda k: keep[k * per_set][1].copy_(keep[k * per_set][0]))
+        t_add = train_of(lambda k: torch.add(keep[k * per_set][0], keep[k * per_set][2], out=keep[k * per_set][3]))
+        t_fwd = train_of(forward)
+        t_bwd = train_of(backward)
+        floors = {"note": "us per launch, back-to-back launches over the same cold ring, one event pair "
+                          "around the whole train",
+                  "torch_copy_us": round(t_copy, 2), "fq_forward_us": round(t_fwd, 2),
+                  "torch_add_us": round(t_add, 2), "fq_backward_us": round(t_bwd, 2)}
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import fq_oracle
@@ -291,6 +322,7 @@ def main():
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "streaming_context": floors,
     }
     print(json.dumps(out))
 
