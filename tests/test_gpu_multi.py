@@ -66,6 +66,26 @@ def test_multi_equals_single_calls_bitwise():
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), name
 
 
+def test_list_of_a_thousand_tiny_tensors():
+    """1000 tensors of 0..3000 elements each, every dtype / granularity / code range: the block ->
+    tensor search, the descriptor table and the per-channel finalisation across many members."""
+    rng = np.random.default_rng(99)
+    cases = []
+    for t in range(1000):
+        dtype = np.float16 if rng.integers(0, 2) else np.float32
+        c = int(rng.integers(1, 6))
+        outer = int(rng.integers(1, 4))
+        inner = int(rng.integers(0, 200)) if t % 97 else 0           # a few empty members
+        if rng.integers(0, 2) == 0:
+            outer, c, inner = 1, 1, outer * c * inner                 # per-tensor
+        qmin, qmax = [(-128, 127), (-8, 7), (-127, 127)][int(rng.integers(0, 3))]
+        x = (rng.standard_normal((outer, c, inner)) * 2).astype(dtype)
+        gy = rng.standard_normal((outer, c, inner)).astype(dtype)
+        theta = workloads.theta_for_scale(rng.uniform(0.01, 0.5, c))
+        cases.append(workloads.TensorCase("t%d" % t, x.shape, outer, c, inner, qmin, qmax, x, theta, gy))
+    _run_list(cases, "multi/thousand")
+
+
 @pytest.mark.timeout(600)
 def test_plan_replay_equals_direct_calls_bitwise():
     """fq_plan_create once, fq_plan_run several times with changing data and theta: every replay
