@@ -332,3 +332,32 @@ def test_more_than_2_31_elements():
         torch.cuda.synchronize()
         pieces.append(float(gsp.item()))
     assert abs(total - sum(pieces)) <= 1e-6 * sum(abs(p) for p in pieces), (total, pieces)
+
+
+def test_randomised_shapes_alignments_and_flags():
+    """Eighty seeded random single-tensor cases: extents (including chunk boundaries +-1), dtype,
+    code range, scale clamp, base misalignment, NO_DX / TWO_PASS flags."""
+    rng = np.random.default_rng(777)
+    edges = [1, 2, 63, 64, 65, 511, 512, 513, 1279 * 4, 1280 * 4, 1280 * 4 + 1, 1280 * 8 - 1, 1280 * 8,
+             1280 * 8 + 3, 2 * 1280 * 8 + 5]
+    for k in range(80):
+        dtype = np.float16 if rng.integers(0, 2) else np.float32
+        inner = int(rng.choice(edges)) if rng.integers(0, 2) else int(rng.integers(1, 30000))
+        outer, c = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        if outer * c * inner > 400_000:
+            outer = 1
+        qmin, qmax = [(-128, 127), (-127, 127), (-8, 7), (0, 15), (-2048, 2047)][int(rng.integers(0, 5))]
+        flags = int(rng.choice([0, 0, fq.FQ_FLAG_NO_DX, fq.FQ_FLAG_TWO_PASS, fq.FQ_FLAG_NO_DX | fq.FQ_FLAG_TWO_PASS]))
+        spread = float(np.exp(rng.uniform(-3, 3)))
+        x = (rng.standard_normal((outer, c, inner)) * spread).astype(dtype)
+        gy = rng.standard_normal((outer, c, inner)).astype(dtype)
+        s = spread * rng.uniform(0.5, 4.0, c) / max(abs(qmin), qmax) * rng.choice([0.2, 1.0, 1.0, 3.0], c)
+        kw = {}
+        if rng.integers(0, 3) == 0:
+            kw = dict(eps=float(rng.uniform(0, 1e-3)), s_min=float(s.min() * 1.5), s_max=float(s.max() * 0.9))
+            if kw["s_max"] < kw["s_min"]:
+                kw["s_max"] = kw["s_min"]
+        case = workloads.TensorCase("rnd%d" % k, x.shape, outer, c, inner, qmin, qmax, x,
+                                    workloads.theta_for_scale(s), gy, **kw)
+        _fwd_bwd(case, "random[%d]" % k, flags=flags, misalign=int(rng.integers(0, 8)),
+                 want_q=(qmin >= -128 and qmax <= 127))
