@@ -67,8 +67,8 @@ def main():
                     help="put no timing events into the timed region (roofline becomes null)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (got --gpus %d); "
-                 "the path shards by tensor / channel range, see DESIGN.md" % args.gpus)
+        sys.exit("bench.py: this library runs on one GPU (got --gpus %d); several GPUs would each take "
+                 "their own tensors or channel ranges, which this benchmark does not launch" % args.gpus)
 
     import numpy as np
     import torch
