@@ -182,7 +182,8 @@ def main():
     record_before = {}                      # launch index -> events to record just before it
     brackets = []
     if not args.no_kernel_events:
-        for n, i in enumerate(range(EVENT_EVERY - 1, args.steps, EVENT_EVERY)):
+        every = min(EVENT_EVERY, max(2, args.steps // 4))        # short runs still get both kinds
+        for n, i in enumerate(range(every - 1, args.steps, every)):
             first = i * per_step
             span = 2 if n % 2 == 0 else 1
             if first + span > len(timed):
