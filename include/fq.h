@@ -165,14 +165,20 @@ fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode,
  * workspace must stay allocated at the same addresses, the workspace must not be written by
  * anything else (one workspace per plan; zero it before fq_plan_create for backward plans), and
  * fq_plan_run must be ordered after fq_plan_create's stream work.  Tensor contents and theta may
- * change freely between runs.  Descriptors with a fused Adam step are refused
- * (FQ_ERR_OPTIMIZER): its bias corrections change with every step, use fq_multi_tensor for
- * those.  fq_plan_destroy frees the host-side plan only (NULL is allowed).
+ * change freely between runs.  fq_plan_destroy frees the host-side plan only (NULL is allowed).
+ *
+ * Backward plans whose descriptors carry a fused Adam step: fq_plan_run repeats the step number
+ * the plan was created with; fq_plan_run_adam(plan, step, stream) first brings the bias
+ * corrections 1-beta^step of every such tensor up to date (one small asynchronous copy of the
+ * table on `stream`, skipped when `step` is the one already in place), then launches.  It is the
+ * call for a training loop: step = 1, 2, 3, ...  (It does host work beyond the launch, so capture
+ * fq_plan_run, not this, in a graph.)
  */
 typedef struct fq_plan fq_plan;
 fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,
                          void *hip_stream, fq_plan **plan);
 fq_status fq_plan_run(const fq_plan *plan, void *hip_stream);
+fq_status fq_plan_run_adam(fq_plan *plan, int64_t step, void *hip_stream);
 void fq_plan_destroy(fq_plan *plan);
 
 /* Static, NUL-terminated description of a status code. */

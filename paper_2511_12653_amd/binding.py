@@ -131,6 +131,8 @@ _lib.fq_plan_create.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_int, ctypes.c
 _lib.fq_plan_create.restype = ctypes.c_int
 _lib.fq_plan_run.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
 _lib.fq_plan_run.restype = ctypes.c_int
+_lib.fq_plan_run_adam.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+_lib.fq_plan_run_adam.restype = ctypes.c_int
 _lib.fq_plan_destroy.argtypes = [ctypes.c_void_p]
 _lib.fq_plan_destroy.restype = None
 _lib.fq_status_string.argtypes = [ctypes.c_int]
@@ -225,6 +227,10 @@ def fq_plan_create(tensors, mode, workspace, stream=None):
 
 def fq_plan_run(plan, stream=None):
     _check(_lib.fq_plan_run(plan, _stream(stream)))
+
+
+def fq_plan_run_adam(plan, step, stream=None):
+    _check(_lib.fq_plan_run_adam(plan, int(step), _stream(stream)))
 
 
 def fq_plan_destroy(plan):

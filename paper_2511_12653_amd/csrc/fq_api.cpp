@@ -262,6 +262,7 @@ struct Prepared {
     int mode = 0;
     long long blocks = 0, channels = 0;
     bool emit_q = false, two_pass = false, any_empty_with_channels = false;
+    std::vector<DevTensor> table;     // host copy of the device descriptors
 };
 
 // Validate, plan, build the device descriptors and (for table launches) copy them to the head of
@@ -281,7 +282,7 @@ fq_status prepare(const fq_tensor *ts, int n, int mode, bool use_table, void *wo
         if (!workspace || ws_bytes < L.total) return FQ_ERR_WORKSPACE;
         if (!aligned(workspace, kAlign)) return FQ_ERR_ALIGN;
     }
-    std::vector<DevTensor> table;
+    std::vector<DevTensor> &table = P.table;
     build_table(ts, n, L, (char *)workspace, table);
     if (use_table) {
         P.args.table = (const DevTensor *)workspace;
@@ -375,6 +376,10 @@ fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode, void *workspace,
 
 struct fq_plan {
     fq::Prepared prepared;
+    void *workspace = nullptr;
+    std::vector<double> beta1, beta2;     // per tensor; unused where the tensor has no Adam step
+    std::vector<char> has_adam;
+    int64_t step = 0;                      // Adam step the device table currently holds
 };
 
 fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,
@@ -382,15 +387,23 @@ fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, 
 {
     if (!plan) return FQ_ERR_NULL;
     *plan = nullptr;
-    // a plan freezes its descriptors, and Adam's bias corrections change with every step
-    for (int i = 0; ts && i < n; ++i)
-        if (ts[i].adam) return FQ_ERR_OPTIMIZER;
     fq_plan *p = new (std::nothrow) fq_plan();
     if (!p) return FQ_ERR_LAUNCH;
     fq_status st = fq::prepare(ts, n, mode, true, workspace, ws_bytes, hip_stream, p->prepared);
     if (st != FQ_OK) {
         delete p;
         return st;
+    }
+    p->workspace = workspace;
+    p->beta1.resize((size_t)n); p->beta2.resize((size_t)n); p->has_adam.resize((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        const bool on = mode == FQ_MODE_BACKWARD && ts[i].adam && ts[i].channels > 0;
+        p->has_adam[(size_t)i] = on ? 1 : 0;
+        if (on) {
+            p->beta1[(size_t)i] = ts[i].adam->beta1;
+            p->beta2[(size_t)i] = ts[i].adam->beta2;
+            p->step = ts[i].adam->step;
+        }
     }
     *plan = p;
     return FQ_OK;
@@ -399,6 +412,27 @@ fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, 
 fq_status fq_plan_run(const fq_plan *plan, void *hip_stream)
 {
     if (!plan) return FQ_ERR_NULL;
+    return fq::launch_prepared(plan->prepared, hip_stream);
+}
+
+fq_status fq_plan_run_adam(fq_plan *plan, int64_t step, void *hip_stream)
+{
+    if (!plan) return FQ_ERR_NULL;
+    if (step < 1) return FQ_ERR_OPTIMIZER;
+    if (step != plan->step) {
+        bool any = false;
+        std::vector<fq::DevTensor> &table = plan->prepared.table;
+        for (size_t i = 0; i < table.size(); ++i) {
+            if (!plan->has_adam[i]) continue;
+            any = true;
+            table[i].adam_bc1 = (float)(1.0 - std::pow(plan->beta1[i], (double)step));
+            table[i].adam_bc2 = (float)(1.0 - std::pow(plan->beta2[i], (double)step));
+        }
+        if (any && fq::copy_table_async(plan->workspace, table.data(), table.size() * sizeof(fq::DevTensor),
+                                        hip_stream) != 0)
+            return FQ_ERR_LAUNCH;
+        plan->step = step;
+    }
     return fq::launch_prepared(plan->prepared, hip_stream);
 }
 

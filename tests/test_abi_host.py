@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(fq):
     names = re.findall(r"\b(fq_[a-z_]+)\s*\(", hdr)
     assert set(names) >= {"fq_forward", "fq_backward", "fq_multi_tensor", "fq_workspace_bytes",
                           "fq_validate", "fq_status_string", "fq_workspace_init", "fq_plan_create",
-                          "fq_plan_run", "fq_plan_destroy"}
+                          "fq_plan_run", "fq_plan_run_adam", "fq_plan_destroy"}
     lib = ctypes.CDLL(fq.library_path())
     for n in set(names):
         assert getattr(lib, n) is not None

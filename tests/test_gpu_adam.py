@@ -82,27 +82,51 @@ def test_adam_skips_non_finite_gradient_and_clamped_channels():
     assert out_d[2].item() != -9.0                                        # momentum still moves it
 
 
-def test_adam_in_a_multi_tensor_call_and_not_in_a_plan():
+def test_adam_in_multi_tensor_calls_and_plans():
+    """Three Adam steps over a list, once through fq_multi_tensor (descriptors rebuilt per step)
+    and once through a plan replayed with fq_plan_run_adam: identical bits, and equal to the
+    oracle after the first step."""
     cases = workloads.multi_tensor_mixed(n_act=4, n_wgt=3, target_bytes=6 << 20, max_batch=2)
-    H.say("adam multi: %d tensors" % len(cases))
-    dcs = [H.DeviceCase(cs, want_q=False) for cs in cases]
-    state = []
-    for cs, d in zip(cases, dcs):
-        m_d, v_d = torch.zeros(cs.channels, device="cuda"), torch.zeros(cs.channels, device="cuda")
-        d.desc.set_adam(fq.FqAdam.from_torch(m_d, v_d, d.theta, step=1, **HYPER))     # in place
-        state.append((m_d, v_d))
-    arr = fq.fq_tensor_array([d.desc for d in dcs])
-    ws = H.workspace_for(arr, fq.FQ_MODE_BACKWARD)
-    with pytest.raises(fq.FqError) as e:
-        fq.fq_plan_create(arr, fq.FQ_MODE_BACKWARD, ws)
-    assert e.value.status == -10
-    fq.fq_multi_tensor(arr, fq.FQ_MODE_BACKWARD, ws)
-    torch.cuda.synchronize()
-    for cs, d, (m_d, v_d) in zip(cases, dcs, state):
-        s, active = fq_oracle.scale(cs.theta)
-        r = fq_oracle.backward(cs.x, cs.gy, s, cs.theta, active, cs.qmin, cs.qmax, cs.outer, cs.channels, cs.inner)
-        z = np.zeros(cs.channels, np.float32)
-        th_ref, m_ref, v_ref = fq_oracle.adam(r["gtheta"], z, z, cs.theta, step=1, **HYPER)
-        _close(d.theta.cpu().numpy(), th_ref, cs.name + " theta")
-        _close(m_d.cpu().numpy(), m_ref, cs.name + " m")
-        _close(v_d.cpu().numpy(), v_ref, cs.name + " v")
+    H.say("adam multi + plan: %d tensors" % len(cases))
+
+    def fresh():
+        dcs = [H.DeviceCase(cs, want_q=False) for cs in cases]
+        state = [(torch.zeros(cs.channels, device="cuda"), torch.zeros(cs.channels, device="cuda")) for cs in cases]
+        return dcs, state
+
+    def attach(dcs, state, step):
+        for d, (m_d, v_d) in zip(dcs, state):
+            d.desc.set_adam(fq.FqAdam.from_torch(m_d, v_d, d.theta, step=step, **HYPER))     # in place
+        return fq.fq_tensor_array([d.desc for d in dcs])
+
+    # (a) fq_multi_tensor, descriptors rebuilt for each step
+    dcs_a, st_a = fresh()
+    ws_a = H.workspace_for(attach(dcs_a, st_a, 1), fq.FQ_MODE_BACKWARD)
+    for step in (1, 2, 3):
+        fq.fq_multi_tensor(attach(dcs_a, st_a, step), fq.FQ_MODE_BACKWARD, ws_a)
+        torch.cuda.synchronize()
+        if step == 1:
+            for cs, d, (m_d, v_d) in zip(cases, dcs_a, st_a):
+                s, active = fq_oracle.scale(cs.theta)
+                r = fq_oracle.backward(cs.x, cs.gy, s, cs.theta, active, cs.qmin, cs.qmax, cs.outer,
+                                       cs.channels, cs.inner)
+                z = np.zeros(cs.channels, np.float32)
+                th_ref, m_ref, v_ref = fq_oracle.adam(r["gtheta"], z, z, cs.theta, step=1, **HYPER)
+                _close(d.theta.cpu().numpy(), th_ref, cs.name + " theta")
+                _close(m_d.cpu().numpy(), m_ref, cs.name + " m")
+                _close(v_d.cpu().numpy(), v_ref, cs.name + " v")
+
+    # (b) one plan, replayed
+    dcs_b, st_b = fresh()
+    arr = attach(dcs_b, st_b, 1)
+    ws_b = H.workspace_for(arr, fq.FQ_MODE_BACKWARD)
+    plan = fq.fq_plan_create(arr, fq.FQ_MODE_BACKWARD, ws_b)
+    try:
+        for step in (1, 2, 3):
+            fq.fq_plan_run_adam(plan, step)
+        torch.cuda.synchronize()
+    finally:
+        fq.fq_plan_destroy(plan)
+    for da, db, (ma, va), (mb, vb) in zip(dcs_a, dcs_b, st_a, st_b):
+        for x, y in ((da.theta, db.theta), (ma, mb), (va, vb), (da.gx, db.gx), (da.gs, db.gs)):
+            assert torch.equal(x.view(torch.uint8), y.view(torch.uint8))
