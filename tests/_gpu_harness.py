@@ -14,6 +14,8 @@ from paper_2511_12653_amd import binding as fq
 from oracle import fq_oracle
 
 GS_RTOL = 1e-5
+GUARD = 8
+SENTINEL = -24576.0          # exactly representable in FP16 and FP32
 
 
 def say(msg):
@@ -53,12 +55,16 @@ class DeviceCase:
         n = case.numel
         tdt = torch.float16 if case.x.dtype == np.float16 else torch.float32
 
+        self._guards = []
+
         def buf(src=None):
-            # `misalign` elements of slack in front, so base pointers can be off the 16-byte grid
-            t = torch.empty(n + misalign, dtype=tdt, device="cuda")
-            v = t[misalign:]
+            # `misalign` elements of slack in front (base pointers off the 16-byte grid) and eight
+            # behind; both are filled with a sentinel that check_guards() looks for afterwards
+            t = torch.full((n + misalign + GUARD,), SENTINEL, dtype=tdt, device="cuda")
+            v = t[misalign:misalign + n]
             if src is not None:
                 v.copy_(dev(src.reshape(-1)))
+            self._guards.append((t, misalign, n))
             return v
 
         self.x = buf(case.x)
@@ -79,6 +85,12 @@ class DeviceCase:
             gtheta=self.gtheta, eps=case.eps, s_min=case.s_min, s_max=case.s_max,
             flags=flags | case.flags,
             dtype=fq.FQ_F16 if case.x.dtype == np.float16 else fq.FQ_F32)
+
+    def check_guards(self, label=""):
+        """Nothing may be written outside [base, base + numel)."""
+        for t, front, n in self._guards:
+            assert bool(torch.all(t[:front] == SENTINEL)) and bool(torch.all(t[front + n:] == SENTINEL)), \
+                label + ": wrote outside a tensor"
 
     def host(self, name):
         t = getattr(self, name)
@@ -104,6 +116,7 @@ def oracle_backward(case, s, active, want_gx=True):
 
 def check_forward(dc, ref=None, label=""):
     case = dc.case
+    dc.check_guards(label)
     s, active, y, q = ref if ref is not None else oracle_forward(case)
     if dc.s is not None and case.channels:
         gs_ = dc.host("s")
@@ -123,6 +136,7 @@ def check_forward(dc, ref=None, label=""):
 
 def check_backward(dc, s, active, label="", want_gx=True):
     case = dc.case
+    dc.check_guards(label)
     r = oracle_backward(case, s, active, want_gx=want_gx)
     if want_gx and case.numel:
         ggx = dc.host("gx").reshape(-1)
