@@ -1,0 +1,54 @@
+"""Repeat the backward pass many times on the same inputs and workspace: the cross-block
+combination (atomic exchange for two blocks per channel, tickets for more) must hand every
+channel's finisher the other blocks' sums of THIS launch -- a stale or missing sum would change
+bits.  Outputs are poisoned before every launch and compared on the device."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_12653_amd import workloads
+from paper_2511_12653_amd import binding as fq
+
+import _gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _repeat(case, label, iters):
+    H.say("%s: %d launches" % (label, iters))
+    dc = H.DeviceCase(case, want_q=False)
+    ws = H.workspace_for(dc.desc, fq.FQ_MODE_BACKWARD)
+    fq.fq_backward(dc.desc, ws)
+    torch.cuda.synchronize()
+    ref = H.oracle_forward(case)
+    H.check_backward(dc, ref[0], ref[1], label)
+    want = [t.clone() for t in (dc.gs, dc.gtheta, dc.gx)]
+    bad = torch.zeros((), dtype=torch.int64, device="cuda")
+    for _ in range(iters):
+        dc.gs.fill_(float("nan"))
+        dc.gtheta.fill_(float("nan"))
+        fq.fq_backward(dc.desc, ws)
+        for got, w in zip((dc.gs, dc.gtheta), want[:2]):
+            bad += (got.view(torch.int32) != w.view(torch.int32)).sum()
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0, "%s: %d mismatching words over %d launches" % (label, int(bad.item()), iters)
+    assert torch.equal(dc.gx.view(torch.uint8), want[2].view(torch.uint8))
+
+
+def test_two_blocks_per_channel_exchange():
+    case = workloads.make("feature_fp16_per_channel")[0]            # 384 channels x 2 blocks
+    _repeat(case, "stress/exchange", 300)
+
+
+def test_many_blocks_per_channel_tickets():
+    case = workloads.train_batch_fp16(shape=(6, 64, 120, 160))[0]   # 64 channels x 12 blocks
+    _repeat(case, "stress/tickets", 200)
+
+
+def test_one_channel_many_blocks():
+    rng = np.random.default_rng(5)
+    n = 3_000_000                                                   # one channel, 586 blocks
+    x = (rng.standard_normal(n) * 2).astype(np.float32)
+    gy = rng.standard_normal(n).astype(np.float32)
+    case = workloads.TensorCase("one", (n,), 1, 1, n, -128, 127, x, workloads.theta_for_scale([0.03]), gy)
+    _repeat(case, "stress/one_channel", 200)
