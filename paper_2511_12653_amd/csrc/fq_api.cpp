@@ -158,7 +158,8 @@ fq_status make_layout(const fq_tensor *ts, int n, int mode, Layout &L)
 }
 
 // Fill the device descriptors; partial/counter pointers are carved out of the workspace.
-void build_table(const fq_tensor *ts, int n, const Layout &L, char *workspace, std::vector<DevTensor> &out)
+void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *workspace,
+                 std::vector<DevTensor> &out)
 {
     out.resize((size_t)n);
     long long block = 0, chan = 0;
@@ -184,7 +185,7 @@ void build_table(const fq_tensor *ts, int n, const Layout &L, char *workspace, s
         d.hi = (float)t.qmax;
         d.eps = t.eps; d.s_min = t.s_min; d.s_max = t.s_max;
         d.flags = t.flags;
-        if (t.adam && t.channels > 0) {
+        if (mode == FQ_MODE_BACKWARD && t.adam && t.channels > 0) {   // validated for this mode only
             const fq_adam &a = *t.adam;
             d.adam_m = a.m; d.adam_v = a.v; d.adam_theta_out = a.theta_out;
             d.adam_lr = (float)a.lr;
@@ -283,7 +284,7 @@ fq_status prepare(const fq_tensor *ts, int n, int mode, bool use_table, void *wo
         if (!aligned(workspace, kAlign)) return FQ_ERR_ALIGN;
     }
     std::vector<DevTensor> &table = P.table;
-    build_table(ts, n, L, (char *)workspace, table);
+    build_table(ts, n, mode, L, (char *)workspace, table);
     if (use_table) {
         P.args.table = (const DevTensor *)workspace;
         if (copy_table_async(workspace, table.data(), (size_t)n * sizeof(DevTensor), stream) != 0)
