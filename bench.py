@@ -72,6 +72,8 @@ def main():
 
     import numpy as np
     import torch
+    from paper_2511_12653_amd import build as lib_build
+    lib_build.ensure_built()
     from paper_2511_12653_amd import binding as fq
     from paper_2511_12653_amd import workloads
 

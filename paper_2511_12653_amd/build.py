@@ -35,5 +35,10 @@ def build(force: bool = True, extra=()) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only if no library is there (tests, smoke and bench load what is built)."""
+    return LIB if os.path.exists(LIB) else build(force=True)
+
+
 if __name__ == "__main__":
     print(build())

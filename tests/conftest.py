@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # test modules import the binding at collection time: load what is built, compile only if
+    # nothing is
+    from paper_2511_12653_amd import build
+    build.ensure_built()
 
 
 @pytest.fixture(scope="session")
