@@ -293,7 +293,9 @@ def main():
             n_sample += cs.numel
         sample_bytes = sum((5 * cs.itemsize if train else cs.itemsize + 1) * cs.numel for cs in sample)
         reps, times = 3, []
-        for _ in range(reps):
+        rep = 0
+        while rep < reps:
+            rep += 1
             c0 = time.perf_counter()
             for cs in sample:
                 s_, active = fq_oracle.scale(cs.theta, cs.eps, cs.s_min, cs.s_max)
@@ -302,6 +304,8 @@ def main():
                     fq_oracle.backward(cs.x, cs.gy, s_, cs.theta, active, cs.qmin, cs.qmax,
                                        cs.outer, cs.channels, cs.inner)
             times.append(time.perf_counter() - c0)
+            if rep == 1:                      # aim at about 5 s of CPU work, 3 to 15 repetitions
+                reps = int(min(15, max(3, round(5.0 / max(times[0], 1e-3)))))
         med = sorted(times)[len(times) // 2]
         cpu = {"value": round(sample_bytes / med / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": "%d of %d tensors of the workload (%d elements, %s), median of %d runs, "
