@@ -277,3 +277,55 @@ void fqo_adam(const float *g, int64_t C, float lr, float beta1, float one_minus_
         theta_out[c] = theta_in[c] - (lr * mhat) / (sqrtf(vhat) + eps);
     }
 }
+
+/* ---- distillation loss between student and teacher feature maps ----------- */
+/*
+ * One (student, teacher) pair of Eq. (7):  L = MSE(a, b) + lambda * (1 - CosSim(a, b)),
+ * a, b: [N, C, M] contiguous (M = H*W).  The paper prints neither lambda, nor the axis of the
+ * cosine, nor how it is averaged; the reading taken (what patch matching needs, and what the
+ * per-operator code `cosine_similarity(a, b, dim=1).mean()` computes):
+ *   mse    = mean over all N*C*M elements of (a - b)^2
+ *   cos_p  = sum_c a b / (max(||a_p||, eps) * max(||b_p||, eps))   for every position p = (n, m),
+ *            norms over the channel axis
+ *   cosim  = mean over the N*M positions of cos_p
+ * out[0] = mse, out[1] = cosim, out[2] = L.  If ga != NULL it receives upstream * dL/da in the
+ * tensors' dtype: 2(a-b)/(N*C*M) - lambda/(N*M) * d cos_p / d a, with
+ * d cos_p / d a_c = b_c / (na' * nb') - [ ||a_p|| > eps ] * cos_p * a_c / ||a_p||^2
+ * (a clamped norm is a constant).  All arithmetic in binary64.
+ */
+void fqo_distill(const void *a, const void *b, int dtype, int64_t N, int64_t C, int64_t M,
+                 double lambda, double eps, double upstream, void *ga, double *out)
+{
+    double sum_sq = 0.0, sum_cos = 0.0;
+    const double k1 = 2.0 / ((double)N * (double)C * (double)M);
+    const double k2 = lambda / ((double)N * (double)M);
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t m = 0; m < M; ++m) {
+            double dot = 0.0, na = 0.0, nb = 0.0;
+            for (int64_t c = 0; c < C; ++c) {
+                int64_t i = (n * C + c) * M + m;
+                double av = (double)load_elem(a, dtype, i), bv = (double)load_elem(b, dtype, i);
+                dot += av * bv;
+                na += av * av;
+                nb += bv * bv;
+                sum_sq += (av - bv) * (av - bv);
+            }
+            double ra = sqrt(na), rb = sqrt(nb);
+            double ca = ra > eps ? ra : eps, cb = rb > eps ? rb : eps;
+            double cosp = dot / (ca * cb);
+            sum_cos += cosp;
+            if (ga) {
+                double self = ra > eps ? cosp / na : 0.0;
+                for (int64_t c = 0; c < C; ++c) {
+                    int64_t i = (n * C + c) * M + m;
+                    double av = (double)load_elem(a, dtype, i), bv = (double)load_elem(b, dtype, i);
+                    double dcos = bv / (ca * cb) - self * av;
+                    double g = upstream * (k1 * (av - bv) - k2 * dcos);
+                    store_elem(ga, dtype, i, (float)g);
+                }
+            }
+        }
+    out[0] = sum_sq / ((double)N * (double)C * (double)M);
+    out[1] = sum_cos / ((double)N * (double)M);
+    out[2] = out[0] + lambda * (1.0 - out[1]);
+}

@@ -38,6 +38,9 @@ def lib():
         L.fqo_backward.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, i32, i32,
                                    vp, vp, vp, vp, vp]
         L.fqo_backward.restype = None
+        L.fqo_distill.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, ctypes.c_double, ctypes.c_double,
+                                  ctypes.c_double, vp, vp]
+        L.fqo_distill.restype = None
         L.fqo_adam.argtypes = [vp, i64, f32, f32, f32, f32, f32, f32, f32, f32, vp, vp, vp, vp]
         L.fqo_adam.restype = None
         _LIB = L
@@ -126,3 +129,14 @@ def adam(g, m, v, theta, lr, beta1, beta2, eps, step):
     lr_, b1, omb1, b2, omb2, eps_, bc1, bc2 = adam_constants(lr, beta1, beta2, eps, step)
     lib().fqo_adam(_p(g), g.size, lr_, b1, omb1, b2, omb2, eps_, bc1, bc2, _p(m), _p(v), _p(theta), _p(out))
     return out, m, v
+
+
+def distill(a, b, lam, eps=1e-8, upstream=1.0, want_grad=True):
+    """Eq. (7) for one (student, teacher) pair [N, C, M].  Returns (mse, cosim, loss, ga or None)."""
+    a, b = np.ascontiguousarray(a), np.ascontiguousarray(b)
+    assert a.shape == b.shape and a.ndim == 3 and a.dtype == b.dtype and a.dtype in _DT
+    n, c, m = a.shape
+    ga = np.empty_like(a) if want_grad else None
+    out = np.empty(3, dtype=np.float64)
+    lib().fqo_distill(_p(a), _p(b), _DT[a.dtype], n, c, m, lam, eps, upstream, _p(ga), _p(out))
+    return float(out[0]), float(out[1]), float(out[2]), ga
