@@ -296,7 +296,9 @@ void fqo_adam(const float *g, int64_t C, float lr, float beta1, float one_minus_
 void fqo_distill(const void *a, const void *b, int dtype, int64_t N, int64_t C, int64_t M,
                  double lambda, double eps, double upstream, void *ga, double *out)
 {
-    double sum_sq = 0.0, sum_cos = 0.0;
+    /* the two means run over up to 10^8 terms: accumulate them in long double (64-bit significand
+       on x86-64) so that the oracle's own summation error stays below 1e-13 relative */
+    long double sum_sq = 0.0L, sum_cos = 0.0L;
     const double k1 = 2.0 / ((double)N * (double)C * (double)M);
     const double k2 = lambda / ((double)N * (double)M);
     for (int64_t n = 0; n < N; ++n)
@@ -308,12 +310,12 @@ void fqo_distill(const void *a, const void *b, int dtype, int64_t N, int64_t C, 
                 dot += av * bv;
                 na += av * av;
                 nb += bv * bv;
-                sum_sq += (av - bv) * (av - bv);
+                sum_sq += (long double)((av - bv) * (av - bv));
             }
             double ra = sqrt(na), rb = sqrt(nb);
-            double ca = ra > eps ? ra : eps, cb = rb > eps ? rb : eps;
+            double ca = ra < eps ? eps : ra, cb = rb < eps ? eps : rb;   /* a NaN norm stays NaN */
             double cosp = dot / (ca * cb);
-            sum_cos += cosp;
+            sum_cos += (long double)cosp;
             if (ga) {
                 double self = ra > eps ? cosp / na : 0.0;
                 for (int64_t c = 0; c < C; ++c) {
@@ -325,7 +327,7 @@ void fqo_distill(const void *a, const void *b, int dtype, int64_t N, int64_t C, 
                 }
             }
         }
-    out[0] = sum_sq / ((double)N * (double)C * (double)M);
-    out[1] = sum_cos / ((double)N * (double)M);
+    out[0] = (double)(sum_sq / ((long double)N * (long double)C * (long double)M));
+    out[1] = (double)(sum_cos / ((long double)N * (long double)M));
     out[2] = out[0] + lambda * (1.0 - out[1]);
 }

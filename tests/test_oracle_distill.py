@@ -78,3 +78,18 @@ def test_zero_student_norm_is_clamped(oracle):
     r = _torch_ref(a, b, 1.0, 1e-8, 1.0)
     assert cosim == 0.0 and mse == 1.0
     np.testing.assert_allclose(ga.astype(np.float64), r[3], rtol=1e-6)
+
+
+def test_nan_poisons_its_position_only(oracle):
+    """A NaN in one channel of one position: that position's cosine, hence every channel of its
+    gradient, and the three scalars are NaN (the library routines do the same); nothing else is."""
+    rng = np.random.default_rng(10)
+    a = rng.standard_normal((1, 6, 9)).astype(np.float32)
+    b = rng.standard_normal((1, 6, 9)).astype(np.float32)
+    a[0, 2, 4] = np.nan
+    mse, cosim, loss, ga = oracle.distill(a, b, lam=0.5)
+    r = _torch_ref(a, b, 0.5, 1e-8, 1.0)
+    assert np.isnan(mse) and np.isnan(cosim) and np.isnan(loss)
+    assert np.array_equal(np.isnan(ga), np.isnan(r[3]))
+    assert np.isnan(ga[0, :, 4]).all() and not np.isnan(np.delete(ga, 4, axis=2)).any()
+    np.testing.assert_allclose(np.delete(ga, 4, axis=2), np.delete(r[3], 4, axis=2), rtol=1e-6)
