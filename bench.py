@@ -47,6 +47,101 @@ WORKLOAD_TEXT = {
 }
 
 
+def distill_bench(args, cases, fq, torch, np):
+    """--pass distill: fq_distill_loss (loss and gradient with respect to the student) on one
+    student/teacher pair shaped like the workload's tensor.  A step is one call (three kernels).
+    Algorithmic bytes per element: read student, read teacher, write the gradient = 3 b; the
+    second read of the pair by the gradient kernel and the per-position statistics are the
+    implementation's own traffic and are not counted."""
+    if len(cases) != 1:
+        sys.exit("bench.py: --pass distill takes a single-tensor workload")
+    cs = cases[0]
+    io_bytes = cs.numel * cs.itemsize
+    set_bytes = 3 * io_bytes
+    ring = max(2, RING_BYTES // set_bytes) if set_bytes < RING_BYTES else 1
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    hs, ht = torch.from_numpy(cs.x.reshape(-1)), torch.from_numpy(cs.gy.reshape(-1))
+    out = torch.zeros(3, dtype=torch.float64, device="cuda")
+    descs, keep = [], []
+    for _ in range(ring):
+        a, b = hs.cuda(), ht.cuda()
+        g = torch.empty_like(a)
+        keep.append((a, b, g))
+        descs.append(fq.FqDistill.from_torch(cs.outer, cs.channels, cs.inner, a, b, out, g, lam=0.5))
+    ws_bytes = fq.fq_distill_workspace_bytes(descs[0])
+    ws = torch.empty(ws_bytes // 8, dtype=torch.float64, device="cuda")
+
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+
+    def new_event():
+        e = ctypes.c_void_p()
+        if hip.hipEventCreate(ctypes.byref(e)) != 0:
+            sys.exit("bench.py: hipEventCreate failed")
+        return e
+
+    for i in range(args.warmup):
+        fq.fq_distill_loss(descs[i % ring], ws, stream)
+    torch.cuda.synchronize()
+    ev_a, ev_z = new_event(), new_event()
+    t0 = time.perf_counter()
+    hip.hipEventRecord(ev_a, sp)
+    for i in range(args.steps):
+        fq.fq_distill_loss(descs[(args.warmup + i) % ring], ws, stream)
+    hip.hipEventRecord(ev_z, sp)
+    t_enq = time.perf_counter()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = ctypes.c_float()
+    hip.hipEventElapsedTime(ctypes.byref(ms), ev_a, ev_z)
+    sec_per_step = (t1 - t0) / args.steps
+    gpu_sec_per_step = ms.value * 1e-3 / args.steps
+    step_bytes = 3 * io_bytes
+    value = step_bytes / sec_per_step / 1e9
+    achieved = step_bytes / gpu_sec_per_step / 1e9
+    roofline = {"bound": "hbm", "kernel": "fq_distill_loss: stats + coef + grad kernels of one call",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": step_bytes, "avg_us": round(gpu_sec_per_step * 1e6, 2),
+                "method": "one HIP event pair on the launch stream around all timed calls, divided by "
+                          "the number of calls"}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import fq_oracle
+        fq_oracle.lib()
+        x3 = cs.x.reshape(cs.outer, cs.channels, cs.inner)
+        t3 = cs.gy.reshape(cs.outer, cs.channels, cs.inner)
+        take = max(1, min(cs.outer, 40_000_000 // max(1, cs.channels * cs.inner)))
+        x3, t3 = x3[:take], t3[:take]
+        reps, times, rep = 3, [], 0
+        while rep < reps:
+            rep += 1
+            c0 = time.perf_counter()
+            fq_oracle.distill(x3, t3, 0.5)
+            times.append(time.perf_counter() - c0)
+            if rep == 1:
+                reps = int(min(15, max(3, round(5.0 / max(times[0], 1e-3)))))
+        med = sorted(times)[len(times) // 2]
+        cpu = {"value": round(3 * x3.size * cs.itemsize / med / 1e9, 4), "unit": "GB/s", "cores": 1,
+               "kind": "oracle", "sample": "%d of %d images of the pair (%d elements), loss and gradient, "
+                                           "median of %d runs, %.2f s each" % (take, cs.outer, x3.size, reps, med)}
+    print(json.dumps({
+        "metric": "distillation loss + gradient GB/s", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.workload] + ", as one student/teacher pair [n, channels, "
+                               "h*w]: loss of Eq. (7) and its gradient",
+                   "launches_per_step": 3, "elements": cs.numel, "bytes_per_step": step_bytes,
+                   "ring_buffer_sets": int(ring), "workspace_bytes": ws_bytes},
+        "host_enqueue_us_per_step": round((t_enq - t0) / args.steps * 1e6, 2),
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "roofline": roofline, "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,9 +150,10 @@ def main():
     ap.add_argument("--workload", default="feature_fp16_per_channel",
                     help="one of paper_2511_12653_amd.workloads.WORKLOAD_NAMES (default: the headline "
                          "tensor); lists of tensors go through the multi-tensor entry points")
-    ap.add_argument("--pass", dest="which", default="train", choices=["train", "codes"],
+    ap.add_argument("--pass", dest="which", default="train", choices=["train", "codes", "distill"],
                     help="train: forward + STE backward (default); codes: forward that writes only the "
-                         "packed int8 codes")
+                         "packed int8 codes; distill: the distillation loss and its gradient for one "
+                         "student/teacher pair of the workload's shape (single-tensor workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="after the timed region also run N plain device copies of the first tensor "
@@ -86,6 +182,8 @@ def main():
     train = args.which == "train"
 
     cases = workloads.make(args.workload)
+    if args.which == "distill":
+        return distill_bench(args, cases, fq, torch, np)
     if not train:
         cases = [cs for cs in cases if cs.qmin >= -128 and cs.qmax <= 127]
     multi = len(cases) > 1

@@ -181,6 +181,37 @@ fq_status fq_plan_run(const fq_plan *plan, void *hip_stream);
 fq_status fq_plan_run_adam(fq_plan *plan, int64_t step, void *hip_stream);
 void fq_plan_destroy(fq_plan *plan);
 
+/*
+ * Distillation loss between one student and one teacher feature map, and its gradient with
+ * respect to the student (Sec. 3.1, Eq. (7)): the producer of the gy that fq_backward consumes.
+ *   mse   = mean over all n*channels*inner elements of (a - b)^2
+ *   cos_p = <a_p, b_p> / (max(||a_p||, eps) * max(||b_p||, eps))   per position p = (n, m), the
+ *           inner product and the norms running over the channel axis
+ *   cosim = mean of cos_p over the n*inner positions
+ *   loss  = mse + lambda * (1 - cosim)
+ * The paper prints neither lambda nor the axis of the cosine; lambda is a field, and the channel
+ * axis is the reading taken (a patch descriptor is the channel vector at one position).
+ * Writes out[0..2] = mse, cosim, loss (binary64, device memory) and, if gstudent != NULL,
+ * gstudent = upstream * dloss/dstudent in the tensors' dtype (rounded once from binary64; a
+ * clamped norm counts as a constant).  `upstream` is the factor in front of this pair's loss in
+ * the total (Eq. (7) sums the pairs: 1, or the loss scale of an FP16 run).  student / teacher are
+ * contiguous [n, channels, inner]; gstudent may be exactly student or teacher (in place).  Three
+ * launches; no atomics, fixed summation order.  A tensor without elements needs no workspace and
+ * gives NaN for mse and loss (a mean of nothing); cosim is then NaN without positions and 0 with
+ * positions but no channels.  The workspace need not be initialised and may be shared with other calls
+ * that do not overlap in time.
+ */
+typedef struct fq_distill {
+    int64_t n, channels, inner;
+    int32_t dtype;                    /* fq_dtype of student, teacher, gstudent */
+    float lambda, eps, upstream;      /* eps >= 0 (1e-8 is customary); no NaN */
+    const void *student, *teacher;    /* in */
+    void *gstudent;                   /* out, optional */
+    double *out;                      /* out: 3 doubles, 8-byte aligned */
+} fq_distill;
+size_t fq_distill_workspace_bytes(const fq_distill *d);   /* 0 if d does not validate; host only */
+fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *fq_status_string(fq_status status);
 

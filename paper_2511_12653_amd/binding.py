@@ -106,6 +106,32 @@ class FqTensor(ctypes.Structure):
         return t
 
 
+class FqDistill(ctypes.Structure):
+    """Mirror of `struct fq_distill` (host struct; the pointers inside are device pointers)."""
+    _fields_ = [("n", ctypes.c_int64), ("channels", ctypes.c_int64), ("inner", ctypes.c_int64),
+                ("dtype", ctypes.c_int32), ("lam", ctypes.c_float), ("eps", ctypes.c_float),
+                ("upstream", ctypes.c_float),
+                ("student", ctypes.c_void_p), ("teacher", ctypes.c_void_p),
+                ("gstudent", ctypes.c_void_p), ("out", ctypes.c_void_p)]
+
+    @classmethod
+    def from_torch(cls, n, channels, inner, student, teacher, out, gstudent=None, lam=1.0, eps=1e-8,
+                   upstream=1.0):
+        import torch
+        if student.dtype not in (torch.float16, torch.float32):
+            raise TypeError("student must be float16 or float32")
+        for t in (teacher, gstudent):
+            if t is not None and (t.dtype != student.dtype or not t.is_contiguous()):
+                raise TypeError("teacher / gstudent must be contiguous and of the student's dtype")
+        if out.dtype != torch.float64 or out.numel() < 3 or not out.is_contiguous() or not student.is_contiguous():
+            raise TypeError("out must be 3 contiguous float64 values; student must be contiguous")
+        self = cls(n, channels, inner, FQ_F16 if student.dtype == torch.float16 else FQ_F32, lam, eps,
+                   upstream, student.data_ptr(), teacher.data_ptr(),
+                   None if gstudent is None else gstudent.data_ptr(), out.data_ptr())
+        self._keep = (student, teacher, gstudent, out)
+        return self
+
+
 class FqError(RuntimeError):
     def __init__(self, status):
         self.status = int(status)
@@ -135,6 +161,10 @@ _lib.fq_plan_run_adam.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void
 _lib.fq_plan_run_adam.restype = ctypes.c_int
 _lib.fq_plan_destroy.argtypes = [ctypes.c_void_p]
 _lib.fq_plan_destroy.restype = None
+_lib.fq_distill_workspace_bytes.argtypes = [ctypes.POINTER(FqDistill)]
+_lib.fq_distill_workspace_bytes.restype = ctypes.c_size_t
+_lib.fq_distill_loss.argtypes = [ctypes.POINTER(FqDistill), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fq_distill_loss.restype = ctypes.c_int
 _lib.fq_status_string.argtypes = [ctypes.c_int]
 _lib.fq_status_string.restype = ctypes.c_char_p
 
@@ -235,3 +265,12 @@ def fq_plan_run_adam(plan, step, stream=None):
 
 def fq_plan_destroy(plan):
     _lib.fq_plan_destroy(plan)
+
+
+def fq_distill_workspace_bytes(d: FqDistill) -> int:
+    return int(_lib.fq_distill_workspace_bytes(ctypes.byref(d)))
+
+
+def fq_distill_loss(d: FqDistill, workspace, stream=None):
+    p, nbytes = _ws(workspace)
+    _check(_lib.fq_distill_loss(ctypes.byref(d), p, nbytes, _stream(stream)))

@@ -10,8 +10,9 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfq.so")
-SOURCES = [os.path.join(CSRC, "fq_kernels.hip"), os.path.join(CSRC, "fq_api.cpp")]
-HEADERS = [os.path.join(CSRC, "fq_internal.h"), os.path.join(HERE, "..", "include", "fq.h")]
+SOURCES = [os.path.join(CSRC, f) for f in ("fq_kernels.hip", "fq_distill.hip", "fq_api.cpp")]
+HEADERS = [os.path.join(CSRC, "fq_internal.h"), os.path.join(CSRC, "fq_device.h"),
+           os.path.join(HERE, "..", "include", "fq.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
          "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,0 +1,434 @@
+// Distillation loss between a student and a teacher feature map and its gradient with respect to
+// the student (DPVO-QAT++ Sec. 3.1, Eq. (7): MSE plus lambda times one minus the cosine
+// similarity over the channel axis, averaged over positions).  This is the producer of the
+// upstream gradient that the fake-quantization backward consumes.
+//
+// [N, C, M] tensors; a "position" is one (n, m).  The reduction runs ACROSS the channel axis, whose
+// stride is M elements, so the layout is read the way it lies in memory: a wavefront owns 64
+// lanes x V consecutive positions of one image (one coalesced row per channel) and walks over a
+// group of channels, every lane keeping the four sums of its V positions (a.b, a.a, b.b,
+// (a-b)^2) in binary64 registers.  No transposition, no LDS, no atomics:
+//   stats kernel   per (position tile, channel group): partial sums -> workspace
+//   coef kernel    per position: adds the groups in index order, forms cos and the two
+//                  coefficients of the gradient, and block-reduces cos and the squared error
+//   grad kernel    elementwise: ga = k1 (a - b) - cB b + cA a, rounded once to the I/O type;
+//                  its first wavefront also adds the block sums in index order into the 3 results
+// All arithmetic is binary64 (two conversions and five fused multiply-adds per element pair, well
+// under the memory time), so results do not depend on how the channels were grouped beyond
+// rounding at the 1e-16 level, and are reproducible run to run.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/fq.h"
+#include "fq_device.h"
+#include "fq_internal.h"
+
+namespace fq {
+
+using namespace dev;
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kUnrollC = 8;            // channels in flight per wavefront (two loads each)
+constexpr unsigned kTargetWaves = 2048;  // eight wavefronts per compute unit
+constexpr unsigned kMaxGroups = 16;
+
+struct DistillArgs {
+    const void *a, *b;
+    void *ga;
+    double *partial;    // [groups][positions][4]
+    double *coef;       // [positions][2]
+    double *blocksum;   // [coef blocks][2]
+    double *out;        // mse, cosim, loss
+    long long M, P;     // positions per image, positions in total
+    unsigned C, groups, per_group, tiles_per_n, tiles, coef_blocks;
+    double k1u, k2u, eps, lambda, inv_ncm, inv_nm;
+};
+
+template <typename T, int V> struct Pack {
+    typedef T type __attribute__((ext_vector_type(V)));
+    static __device__ __forceinline__ T get(const type &v, int i) { return v[i]; }
+    static __device__ __forceinline__ void set(type &v, int i, T x) { v[i] = x; }
+};
+template <typename T> struct Pack<T, 1> {
+    typedef T type;
+    static __device__ __forceinline__ T get(const type &v, int) { return v; }
+    static __device__ __forceinline__ void set(type &v, int, T x) { v = x; }
+};
+
+typedef double double2v __attribute__((ext_vector_type(2)));
+typedef double double4v __attribute__((ext_vector_type(4)));
+
+// Which tile / channel group a wavefront works on, and where its lane's V positions start.
+struct Where {
+    bool active, valid;
+    unsigned c0, c1;
+    long long first;   // element offset of (n, c0, m0)
+    long long p0;      // position index of the lane's first position
+};
+
+template <int V>
+__device__ __forceinline__ Where locate(const DistillArgs &k, unsigned groups, unsigned per_group)
+{
+    Where w;
+    const unsigned wid = blockIdx.x * kWaves + (threadIdx.x >> 6);
+    w.active = wid < k.tiles * groups;
+    const unsigned tile = w.active ? wid / groups : 0u;
+    const unsigned g = w.active ? wid % groups : 0u;
+    const unsigned n = tile / k.tiles_per_n;
+    const unsigned tn = tile - n * k.tiles_per_n;
+    long long m0 = ((long long)tn * 64 + (threadIdx.x & 63)) * V;
+    w.valid = w.active && m0 < k.M;
+    if (m0 >= k.M) m0 = k.M - V;            // lanes past the end re-read the last vector; results dropped
+    w.c0 = g * per_group;
+    w.c1 = w.c0 + per_group < k.C ? w.c0 + per_group : k.C;
+    if (w.c0 > w.c1) w.c0 = w.c1;
+    w.first = ((long long)n * k.C + w.c0) * k.M + m0;
+    w.p0 = (long long)n * k.M + m0;
+    return w;
+}
+
+template <typename T, int V>
+__global__ __launch_bounds__(kThreads) void distill_stats_kernel(DistillArgs k)
+{
+    typedef typename Pack<T, V>::type VT;
+    const Where w = locate<V>(k, k.groups, k.per_group);
+    if (!w.active) return;
+    const T *a = (const T *)k.a + w.first;
+    const T *b = (const T *)k.b + w.first;
+    double dot[V], na[V], nb[V], sq[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) dot[e] = na[e] = nb[e] = sq[e] = 0.0;
+
+    auto accumulate = [&](const VT &va, const VT &vb) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            const double x = (double)(float)Pack<T, V>::get(va, e);
+            const double y = (double)(float)Pack<T, V>::get(vb, e);
+            const double d = x - y;
+            dot[e] = __builtin_fma(x, y, dot[e]);
+            na[e] = __builtin_fma(x, x, na[e]);
+            nb[e] = __builtin_fma(y, y, nb[e]);
+            sq[e] = __builtin_fma(d, d, sq[e]);
+        }
+    };
+
+    unsigned c = w.c0;
+    for (; c + kUnrollC <= w.c1; c += kUnrollC) {
+        VT ra[kUnrollC], rb[kUnrollC];
+#pragma unroll
+        for (int u = 0; u < kUnrollC; ++u) {
+            ra[u] = ld_global((const VT *)(a + (long long)u * k.M));
+            rb[u] = ld_global((const VT *)(b + (long long)u * k.M));
+        }
+#pragma unroll
+        for (int u = 0; u < kUnrollC; ++u) accumulate(ra[u], rb[u]);
+        a += (long long)kUnrollC * k.M;
+        b += (long long)kUnrollC * k.M;
+    }
+    for (; c < w.c1; ++c) {
+        const VT va = ld_global((const VT *)a), vb = ld_global((const VT *)b);
+        accumulate(va, vb);
+        a += k.M;
+        b += k.M;
+    }
+    if (w.valid) {
+        const unsigned g = w.c0 / k.per_group;
+        double4v *dst = (double4v *)k.partial + ((long long)g * k.P + w.p0);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            double4v o = {dot[e], na[e], nb[e], sq[e]};
+            st_global(dst + e, o);
+        }
+    }
+}
+
+// Sum of `v` over the block in a fixed order; valid in thread 0.
+__device__ __forceinline__ double block_sum(double v, double *lds)
+{
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == kSumLane) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < kWaves; ++i) total += lds[i];
+    }
+    __syncthreads();
+    return total;
+}
+
+__global__ __launch_bounds__(kThreads) void distill_coef_kernel(DistillArgs k)
+{
+    __shared__ double lds[kWaves];
+    const long long p = (long long)blockIdx.x * kThreads + threadIdx.x;
+    double cosp = 0.0, sq = 0.0;
+    if (p < k.P) {
+        double dot = 0.0, na = 0.0, nb = 0.0;
+        const double4v *src = (const double4v *)k.partial + p;
+        for (unsigned g = 0; g < k.groups; ++g) {
+            const double4v v = ld_global(src + (long long)g * k.P);
+            dot += v[0];
+            na += v[1];
+            nb += v[2];
+            sq += v[3];
+        }
+        const double ra = sqrt(na), rb = sqrt(nb);
+        // a NaN norm stays NaN, so a non-finite input poisons its whole position visibly
+        const double ca = ra < k.eps ? k.eps : ra, cb = rb < k.eps ? k.eps : rb;
+        const double inv = 1.0 / (ca * cb);
+        cosp = dot / (ca * cb);
+        const double self = ra > k.eps ? cosp / na : 0.0;
+        if (k.coef) {
+            double2v o = {k.k2u * inv, k.k2u * self};
+            st_global((double2v *)k.coef + p, o);
+        }
+    }
+    const double sc = block_sum(cosp, lds);
+    const double ss = block_sum(sq, lds);
+    if (threadIdx.x == 0) {
+        double2v o = {sc, ss};
+        st_global((double2v *)k.blocksum + blockIdx.x, o);
+    }
+}
+
+// The three results from the per-block sums, added in index order by one wavefront.
+__device__ __forceinline__ void finish(const DistillArgs &k)
+{
+    const unsigned lane = threadIdx.x & 63;
+    double sc = 0.0, ss = 0.0;
+    for (unsigned i = lane; i < k.coef_blocks; i += 64) {
+        const double2v v = ld_global((const double2v *)k.blocksum + i);
+        sc += v[0];
+        ss += v[1];
+    }
+    sc = wave_sum(sc);
+    ss = wave_sum(ss);
+    if (lane == kSumLane) {
+        const double mse = ss * k.inv_ncm, cosim = sc * k.inv_nm;
+        st_global(k.out + 0, mse);
+        st_global(k.out + 1, cosim);
+        st_global(k.out + 2, mse + k.lambda * (1.0 - cosim));
+    }
+}
+
+__global__ __launch_bounds__(64) void distill_finish_kernel(DistillArgs k) { finish(k); }
+
+template <typename T, int V>
+__global__ __launch_bounds__(kThreads) void distill_grad_kernel(DistillArgs k, unsigned groups, unsigned per_group)
+{
+    typedef typename Pack<T, V>::type VT;
+    if (blockIdx.x == 0 && threadIdx.x < 64) finish(k);
+    const Where w = locate<V>(k, groups, per_group);
+    if (!w.active) return;
+    const T *a = (const T *)k.a + w.first;
+    const T *b = (const T *)k.b + w.first;
+    T *ga = (T *)k.ga + w.first;
+    double cb[V], ca[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const double2v v = ld_global((const double2v *)k.coef + w.p0 + e);
+        cb[e] = v[0];
+        ca[e] = v[1];
+    }
+    auto grad = [&](const VT &va, const VT &vb) {
+        VT o;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            const double x = (double)(float)Pack<T, V>::get(va, e);
+            const double y = (double)(float)Pack<T, V>::get(vb, e);
+            double g = k.k1u * (x - y);
+            g = __builtin_fma(-cb[e], y, g);
+            g = __builtin_fma(ca[e], x, g);
+            Pack<T, V>::set(o, e, (T)(float)g);
+        }
+        return o;
+    };
+    constexpr int U = kUnrollC / 2;
+    unsigned c = w.c0;
+    for (; c + U <= w.c1; c += U) {
+        VT ra[U], rb[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ra[u] = ld_stream((const VT *)(a + (long long)u * k.M));
+            rb[u] = ld_stream((const VT *)(b + (long long)u * k.M));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const VT o = grad(ra[u], rb[u]);
+            if (w.valid) st_stream((VT *)(ga + (long long)u * k.M), o);
+        }
+        a += (long long)U * k.M;
+        b += (long long)U * k.M;
+        ga += (long long)U * k.M;
+    }
+    for (; c < w.c1; ++c) {
+        const VT o = grad(ld_stream((const VT *)a), ld_stream((const VT *)b));
+        if (w.valid) st_stream((VT *)ga, o);
+        a += k.M;
+        b += k.M;
+        ga += k.M;
+    }
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Plan {
+    int vec;                 // elements per lane
+    unsigned tiles_per_n, tiles, groups, per_group, grad_groups, grad_per_group, coef_blocks;
+    size_t off_coef, off_blocksum, bytes;
+};
+
+fq_status make_plan(const fq_distill *d, Plan &pl)
+{
+    if (!d) return FQ_ERR_NULL;
+    if (d->dtype != FQ_F16 && d->dtype != FQ_F32) return FQ_ERR_DTYPE;
+    if (d->n < 0 || d->channels < 0 || d->inner < 0) return FQ_ERR_SHAPE;
+    const size_t esz = d->dtype == FQ_F16 ? 2 : 4;
+    // positions index 32-bit grids of 64-lane tiles; the element count must fit in 62 bits
+    if (d->n > 0 && d->inner > (long long)0x7fffffff / d->n) return FQ_ERR_SHAPE;
+    const long long P = d->n * d->inner;
+    if (d->channels > 0x7fffffff) return FQ_ERR_SHAPE;
+    if (P > 0 && d->channels > ((long long)1 << 60) / P) return FQ_ERR_SHAPE;
+    if (!(d->lambda == d->lambda) || !(d->upstream == d->upstream) || !(d->eps >= 0.0f)) return FQ_ERR_SCALE_PARAMS;
+    if (!d->out) return FQ_ERR_NULL;
+    if ((uintptr_t)d->out % sizeof(double)) return FQ_ERR_ALIGN;
+    const bool empty = P == 0 || d->channels == 0;
+    if (!empty) {
+        if (!d->student || !d->teacher) return FQ_ERR_NULL;
+        if ((uintptr_t)d->student % esz || (uintptr_t)d->teacher % esz || (uintptr_t)d->gstudent % esz)
+            return FQ_ERR_ALIGN;
+        if (d->gstudent) {
+            // exact in-place over the student is fine (each element is read before it is written
+            // by the same lane); any other overlap is not
+            const char *g0 = (const char *)d->gstudent, *g1 = g0 + (size_t)P * d->channels * esz;
+            const void *ins[2] = {d->student, d->teacher};
+            for (const void *in : ins) {
+                const char *i0 = (const char *)in, *i1 = i0 + (size_t)P * d->channels * esz;
+                if (g0 != i0 && g0 < i1 && i0 < g1) return FQ_ERR_ALIAS;
+            }
+        }
+    }
+    if (empty) {
+        pl = Plan{};
+        pl.vec = 1;
+        pl.bytes = 256;
+        return FQ_OK;
+    }
+    const int full = (int)(kVecBytes / esz);
+    const bool vec_ok = !empty && d->inner % full == 0 && (uintptr_t)d->student % kVecBytes == 0 &&
+                        (uintptr_t)d->teacher % kVecBytes == 0 && (uintptr_t)d->gstudent % kVecBytes == 0;
+    pl.vec = vec_ok ? full : 1;
+    const long long per_tile = 64LL * pl.vec;
+    const long long tpn = empty ? 0 : (d->inner + per_tile - 1) / per_tile;
+    if (tpn * d->n > 0x3fffffffLL / kMaxGroups) return FQ_ERR_SHAPE;
+    pl.tiles_per_n = (unsigned)tpn;
+    pl.tiles = (unsigned)(tpn * d->n);
+    auto split = [&](unsigned want_waves, unsigned cap, unsigned &groups, unsigned &per_group) {
+        unsigned g = pl.tiles ? (want_waves + pl.tiles - 1) / pl.tiles : 1u;
+        if (g > cap) g = cap;
+        if (g > (unsigned)d->channels) g = (unsigned)d->channels;
+        if (g < 1u) g = 1u;
+        per_group = empty ? 0u : ((unsigned)d->channels + g - 1) / g;
+        groups = per_group ? ((unsigned)d->channels + per_group - 1) / per_group : 1u;
+    };
+    split(kTargetWaves, kMaxGroups, pl.groups, pl.per_group);
+    split(2 * kTargetWaves, 1024u, pl.grad_groups, pl.grad_per_group);
+    if ((unsigned long long)pl.tiles * pl.grad_groups > 0x3fffffffULL) {
+        pl.grad_groups = pl.groups;
+        pl.grad_per_group = pl.per_group;
+    }
+    pl.coef_blocks = (unsigned)((P + kThreads - 1) / kThreads);
+    const size_t partial = align256((size_t)pl.groups * (size_t)P * 4 * sizeof(double));
+    const size_t coef = align256((size_t)P * 2 * sizeof(double));
+    const size_t blocksum = align256((size_t)pl.coef_blocks * 2 * sizeof(double));
+    pl.off_coef = partial;
+    pl.off_blocksum = partial + coef;
+    pl.bytes = partial + coef + blocksum;
+    if (pl.bytes < 256) pl.bytes = 256;
+    return FQ_OK;
+}
+
+__global__ void distill_empty_kernel(double *out, bool has_positions)
+{
+    // a mean over no elements is 0/0; positions without channels have cos = 0 / eps^2 = 0
+    const double nan = __builtin_nan("");
+    out[0] = nan;
+    out[1] = has_positions ? 0.0 : nan;
+    out[2] = nan;
+}
+
+template <typename T, int V>
+fq_status launch(const DistillArgs &k, const Plan &pl, bool want_grad, hipStream_t st)
+{
+    const unsigned stats_blocks = (pl.tiles * pl.groups + kWaves - 1) / kWaves;
+    distill_stats_kernel<T, V><<<stats_blocks, kThreads, 0, st>>>(k);
+    distill_coef_kernel<<<pl.coef_blocks, kThreads, 0, st>>>(k);
+    if (want_grad) {
+        const unsigned grad_blocks = (pl.tiles * pl.grad_groups + kWaves - 1) / kWaves;
+        distill_grad_kernel<T, V><<<grad_blocks, kThreads, 0, st>>>(k, pl.grad_groups, pl.grad_per_group);
+    } else {
+        distill_finish_kernel<<<1, 64, 0, st>>>(k);
+    }
+    return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_LAUNCH;
+}
+
+}  // namespace
+}  // namespace fq
+
+extern "C" {
+
+size_t fq_distill_workspace_bytes(const fq_distill *d)
+{
+    fq::Plan pl;
+    return fq::make_plan(d, pl) == FQ_OK ? pl.bytes : 0;
+}
+
+fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    using namespace fq;
+    Plan pl;
+    const fq_status v = make_plan(d, pl);
+    if (v != FQ_OK) return v;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (d->n * d->inner == 0 || d->channels == 0) {
+        distill_empty_kernel<<<1, 1, 0, st>>>(d->out, d->n * d->inner != 0);
+        return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_LAUNCH;
+    }
+    if (!workspace || ws_bytes < pl.bytes) return FQ_ERR_WORKSPACE;
+    if ((uintptr_t)workspace % 256) return FQ_ERR_ALIGN;
+
+    DistillArgs k;
+    k.a = d->student;
+    k.b = d->teacher;
+    k.ga = d->gstudent;
+    k.partial = (double *)workspace;
+    k.coef = d->gstudent ? (double *)((char *)workspace + pl.off_coef) : nullptr;
+    k.blocksum = (double *)((char *)workspace + pl.off_blocksum);
+    k.out = d->out;
+    k.M = d->inner;
+    k.P = d->n * d->inner;
+    k.C = (unsigned)d->channels;
+    k.groups = pl.groups;
+    k.per_group = pl.per_group;
+    k.tiles_per_n = pl.tiles_per_n;
+    k.tiles = pl.tiles;
+    k.coef_blocks = pl.coef_blocks;
+    const double ncm = (double)d->n * (double)d->channels * (double)d->inner;
+    const double nm = (double)d->n * (double)d->inner;
+    k.k1u = (double)d->upstream * (2.0 / ncm);
+    k.k2u = (double)d->upstream * ((double)d->lambda / nm);
+    k.eps = (double)d->eps;
+    k.lambda = (double)d->lambda;
+    k.inv_ncm = 1.0 / ncm;
+    k.inv_nm = 1.0 / nm;
+    const bool grad = d->gstudent != nullptr;
+    if (d->dtype == FQ_F16)
+        return pl.vec > 1 ? launch<_Float16, 8>(k, pl, grad, st) : launch<_Float16, 1>(k, pl, grad, st);
+    return pl.vec > 1 ? launch<float, 4>(k, pl, grad, st) : launch<float, 1>(k, pl, grad, st);
+}
+
+}  // extern "C"

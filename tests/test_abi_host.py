@@ -24,7 +24,8 @@ def test_exports_every_declared_symbol(fq):
     names = re.findall(r"\b(fq_[a-z_]+)\s*\(", hdr)
     assert set(names) >= {"fq_forward", "fq_backward", "fq_multi_tensor", "fq_workspace_bytes",
                           "fq_validate", "fq_status_string", "fq_workspace_init", "fq_plan_create",
-                          "fq_plan_run", "fq_plan_run_adam", "fq_plan_destroy"}
+                          "fq_plan_run", "fq_plan_run_adam", "fq_plan_destroy",
+                          "fq_distill_loss", "fq_distill_workspace_bytes"}
     lib = ctypes.CDLL(fq.library_path())
     for n in set(names):
         assert getattr(lib, n) is not None
@@ -128,3 +129,54 @@ def test_workspace_bytes(fq):
     with pytest.raises(b.FqError) as e:
         b.fq_forward(_desc(fq, x=None), stream=0)
     assert e.value.status == -1
+
+
+def _distill(fq, **kw):
+    base = dict(n=1, channels=384, inner=19200, dtype=fq.FQ_F16, lam=0.5, eps=1e-8, upstream=1.0,
+                student=0x10000000, teacher=0x20000000, gstudent=0x30000000, out=0x40000000)
+    base.update(kw)
+    return fq.FqDistill(**base)
+
+
+def test_distill_struct_and_workspace(fq):
+    assert ctypes.sizeof(fq.FqDistill) == 3 * 8 + 4 * 4 + 4 * 8
+    # one image of 19200 positions: 38 tiles of 512 positions -> capped at 16 channel groups
+    P = 19200
+    want = 16 * P * 32 + P * 16 + ((P + 255) // 256) * 16
+    got = fq.fq_distill_workspace_bytes(_distill(fq))
+    assert got % 256 == 0 and want <= got < want + 3 * 256
+    # a batch of 15 images: 570 tiles -> 4 groups
+    P = 15 * 19200
+    want = 4 * P * 32 + P * 16 + ((P + 255) // 256) * 16
+    got = fq.fq_distill_workspace_bytes(_distill(fq, n=15))
+    assert want <= got < want + 3 * 256
+    # empty tensors validate and need only the minimum
+    assert fq.fq_distill_workspace_bytes(_distill(fq, n=0)) == 256
+    assert fq.fq_distill_workspace_bytes(_distill(fq, channels=0, student=None, teacher=None)) == 256
+
+
+@pytest.mark.parametrize("kw, status", [
+    (dict(dtype=7), -2), (dict(n=-1), -3), (dict(inner=2 ** 31, n=2), -3), (dict(channels=2 ** 31), -3),
+    (dict(student=None), -1), (dict(teacher=None), -1), (dict(out=None), -1),
+    (dict(out=0x40000004), -5), (dict(student=0x10000001), -5), (dict(gstudent=0x30000001), -5),
+    (dict(eps=-1.0), -7), (dict(lam=float("nan")), -7), (dict(upstream=float("nan")), -7),
+    (dict(gstudent=0x10000000 + 2), -9), (dict(gstudent=0x20000000 - 64), -9),
+])
+def test_distill_rejects(fq, kw, status):
+    d = _distill(fq, **kw)
+    assert fq.fq_distill_workspace_bytes(d) == 0
+    with pytest.raises(fq.FqError) as e:
+        fq.fq_distill_loss(d, (0x50000000, 1 << 40), stream=0)
+    assert e.value.status == status
+
+
+def test_distill_workspace_errors_before_any_launch(fq):
+    d = _distill(fq)
+    need = fq.fq_distill_workspace_bytes(d)
+    for ws, status in [((0, need), -6), ((0x50000000, need - 1), -6), ((0x50000010, need), -5)]:
+        with pytest.raises(fq.FqError) as e:
+            fq.fq_distill_loss(d, ws, stream=0)
+        assert e.value.status == status
+    # in place over the student or the teacher is accepted
+    assert fq.fq_distill_workspace_bytes(_distill(fq, gstudent=0x10000000)) == need
+    assert fq.fq_distill_workspace_bytes(_distill(fq, gstudent=0x20000000)) == need

@@ -1,0 +1,215 @@
+"""GPU parity of fq_distill_loss (Eq. (7), one student/teacher pair) against the binary64 oracle.
+
+Bars: the three scalars agree to 1e-12 (relative for mse and loss, absolute for cosim: both sides
+sum in binary64, only the order differs); the gradient is rounded once from binary64 to the I/O
+type on both sides, so it may differ by at most 1 ulp, and only where the binary64 values straddle
+a rounding boundary (fewer than 1 element in 10^4).  With a single channel the cosine is +-1 and its
+gradient is zero analytically, so what is rounded is the MSE term k (a - b) plus rounding noise of
+the two cancelling cosine terms: for binary32 inputs a - b sits exactly on a rounding midpoint for
+a few percent of the elements and the noise breaks the tie either way; there only the 1-ulp bound
+is asserted."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_12653_amd import binding as fq
+
+import _gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+GUARD = 16
+SENTINEL = 777.0
+
+
+def _pair(seed, shape, dtype, corr=0.8, noise=0.4, scale=1.5):
+    rng = np.random.Generator(np.random.Philox(seed))
+    a = (rng.standard_normal(shape) * scale).astype(dtype)
+    b = (a.astype(np.float64) * corr + rng.standard_normal(shape) * noise).astype(dtype)
+    return a, b
+
+
+def _guarded(src, misalign=0):
+    """Device copy of `src` with sentinel slack on both sides; returns (storage, view)."""
+    t = torch.full((src.size + misalign + GUARD,), SENTINEL, dtype=torch.from_numpy(src[:0].copy()).dtype,
+                   device="cuda")
+    v = t[misalign:misalign + src.size]
+    v.copy_(torch.from_numpy(src.reshape(-1)))
+    return t, v
+
+
+def _run(a, b, lam, oracle, eps=1e-8, upstream=1.0, want_grad=True, inplace=None, misalign=0, label="",
+         noise_floor=0.0):
+    n, c, m = a.shape
+    H.say("distill %s: shape %s %s lam=%g up=%g grad=%s inplace=%s misalign=%d" % (
+        label, a.shape, a.dtype.name, lam, upstream, want_grad, inplace, misalign))
+    eps32, lam32, up32 = float(np.float32(eps)), float(np.float32(lam)), float(np.float32(upstream))
+    ref = oracle.distill(a, b, lam32, eps32, up32, want_grad)
+    sa, da = _guarded(a, misalign)
+    sb, db = _guarded(b, misalign)
+    sg, dg = (None, None)
+    if want_grad:
+        if inplace == "student":
+            sg, dg = sa, da
+        elif inplace == "teacher":
+            sg, dg = sb, db
+        else:
+            sg, dg = _guarded(np.zeros_like(a), misalign)
+    out = torch.full((3,), -1.0, dtype=torch.float64, device="cuda")
+    d = fq.FqDistill.from_torch(n, c, m, da, db, out, dg, lam=lam, eps=eps, upstream=upstream)
+    need = fq.fq_distill_workspace_bytes(d)
+    assert need >= 256 and need % 256 == 0
+    # the workspace need not be initialised: poison it
+    ws = torch.full((need // 8,), float("nan"), dtype=torch.float64, device="cuda")
+    fq.fq_distill_loss(d, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    if a.size == 0:
+        assert np.array_equal(np.isnan(got), np.isnan(np.array(ref[:3])))
+        assert np.isnan(got[0]) and np.isnan(got[2]) and (np.isnan(got[1]) or got[1] == ref[1] == 0.0)
+        return got, None
+    assert abs(got[0] - ref[0]) <= 1e-12 * abs(ref[0]), (label, "mse", got[0], ref[0])
+    assert abs(got[1] - ref[1]) <= 1e-12, (label, "cosim", got[1], ref[1])
+    assert abs(got[2] - ref[2]) <= 1e-12 * max(abs(ref[2]), 1e-3), (label, "loss", got[2], ref[2])
+    for store, view in ((sa, da), (sb, db), (sg, dg)):
+        if store is None:
+            continue
+        h = store.cpu().numpy()
+        assert np.all(h[:misalign] == SENTINEL) and np.all(h[misalign + a.size:] == SENTINEL), (label, "guard")
+    ga = None
+    if want_grad:
+        ga = dg.cpu().numpy().reshape(a.shape)
+        dist = H.ulp_distance(ga, ref[3])
+        # where the gradient cancels to zero analytically both sides hold rounding noise
+        dist[(np.abs(ga) <= noise_floor) & (np.abs(ref[3]) <= noise_floor)] = 0
+        assert dist.max() <= 1, (label, "ga ulp", int(dist.max()))
+        if c > 1:
+            assert (dist != 0).sum() <= max(1, a.size // 10000), (label, "ga mismatches", int((dist != 0).sum()))
+    if inplace != "student":
+        assert np.array_equal(da.cpu().numpy().reshape(a.shape), a)
+    if inplace != "teacher":
+        assert np.array_equal(db.cpu().numpy().reshape(a.shape), b)
+    return got, ga
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("shape", [(2, 48, 960), (3, 37, 1000), (1, 5, 8), (1, 1, 4096), (4, 130, 72)])
+def test_vector_path(oracle, dtype, shape):
+    a, b = _pair(11, shape, dtype)
+    _run(a, b, 0.37, oracle, label="vec")
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("shape, misalign", [((2, 19, 997), 0), ((1, 7, 1), 0), ((2, 24, 960), 1), ((1, 3, 67), 3)])
+def test_scalar_path(oracle, dtype, shape, misalign):
+    a, b = _pair(12, shape, dtype)
+    _run(a, b, 1.0, oracle, misalign=misalign, label="scalar")
+
+
+@pytest.mark.parametrize("inplace", ["student", "teacher"])
+def test_in_place(oracle, inplace):
+    a, b = _pair(13, (2, 40, 520), np.float16)
+    _run(a, b, 0.5, oracle, inplace=inplace, label="inplace")
+
+
+def test_loss_only_and_upstream_scale(oracle):
+    a, b = _pair(14, (2, 33, 640), np.float16, scale=6.0, noise=3.0)
+    got0, _ = _run(a, b, 0.25, oracle, want_grad=False, label="loss-only")
+    got1, g1 = _run(a, b, 0.25, oracle, upstream=1.0, label="up1")
+    got2, g2 = _run(a, b, 0.25, oracle, upstream=1024.0, label="up1024")
+    assert np.array_equal(got0, got1) and np.array_equal(got1, got2)       # scalars do not depend on either
+    # a power-of-two loss scale only shifts exponents (away from binary16's subnormal range)
+    big = np.abs(g1.astype(np.float64)) > 2.0 ** -14
+    assert big.any() and np.array_equal(g2[big].astype(np.float64), g1[big].astype(np.float64) * 1024.0)
+
+
+def test_zero_norm_positions_and_identical_maps(oracle):
+    a, b = _pair(15, (2, 16, 256), np.float32)
+    a[0, :, 5:9] = 0.0          # student norm below eps: the clamp is a constant
+    b[1, :, 100:140] = 0.0      # teacher norm below eps: cos = 0 there
+    a[1, :, 200] = 0.0
+    b[1, :, 200] = 0.0
+    _run(a, b, 0.7, oracle, label="zero-norm")
+    # student == teacher: every term of the gradient cancels; what is left is noise around
+    # 1e-16 of the cancelling terms (themselves below 1e-3 here)
+    got, ga = _run(a, a.copy(), 0.7, oracle, label="identical", noise_floor=1e-18)
+    assert got[0] == 0.0 and np.abs(ga).max() <= 1e-18
+
+
+def test_lambda_zero_is_plain_mse(oracle):
+    a, b = _pair(16, (1, 20, 512), np.float32)
+    got, ga = _run(a, b, 0.0, oracle, label="lam0")
+    ref = 2.0 * (a.astype(np.float64) - b.astype(np.float64)) / a.size
+    np.testing.assert_allclose(ga.astype(np.float64), ref, rtol=2.0 ** -23)
+
+
+def test_empty(oracle):
+    for shape in [(0, 4, 16), (2, 0, 16), (2, 4, 0)]:
+        a = np.zeros(shape, np.float16)
+        _run(a, a.copy(), 0.5, oracle, label="empty")
+
+
+def test_non_finite_inputs_propagate(oracle):
+    a, b = _pair(17, (1, 8, 128), np.float32)
+    a[0, 3, 17] = np.nan
+    n, c, m = a.shape
+    da, db = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
+    dg = torch.zeros_like(da)
+    out = torch.zeros(3, dtype=torch.float64, device="cuda")
+    d = fq.FqDistill.from_torch(n, c, m, da, db, out, dg, lam=0.5)
+    ws = torch.zeros(fq.fq_distill_workspace_bytes(d) // 8, dtype=torch.float64, device="cuda")
+    fq.fq_distill_loss(d, ws)
+    torch.cuda.synchronize()
+    ref = oracle.distill(a, b, 0.5, float(np.float32(1e-8)), 1.0)
+    assert np.all(np.isnan(out.cpu().numpy())) and all(np.isnan(r) for r in ref[:3])
+    g = dg.cpu().numpy()
+    assert np.array_equal(np.isnan(g), np.isnan(ref[3]))
+    assert np.isnan(g[0, :, 17]).all() and not np.isnan(np.delete(g, 17, axis=2)).any()
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("shape", [(1, 384, 120 * 160), (15, 384, 120 * 160)])
+def test_full_size_feature_maps(oracle, shape):
+    """The FP16 feature map of the headline workload (one frame, and a training batch of 15), in
+    the launch configuration that is timed; every element against the oracle."""
+    a, b = _pair(18, shape, np.float16, scale=1.0)
+    _run(a, b, 0.5, oracle, upstream=256.0, label="full")
+
+
+def test_feeds_the_fake_quantization_backward(oracle):
+    """Loss gradient -> gy of fq_backward on the same stream, no host round trip: the chain the
+    distillation step runs (Sec. 3.1)."""
+    rng = np.random.Generator(np.random.Philox(19))
+    n, c, m = 2, 24, 640
+    x = (rng.standard_normal((n, c, m)) * 1.2).astype(np.float16)
+    theta = np.log(np.expm1(rng.uniform(0.01, 0.05, c))).astype(np.float32)
+    teacher = (x.astype(np.float64) + rng.standard_normal((n, c, m)) * 0.02).astype(np.float16)
+
+    dx, dth, dt = torch.from_numpy(x).cuda(), torch.from_numpy(theta).cuda(), torch.from_numpy(teacher).cuda()
+    y, gy, gx = torch.empty_like(dx), torch.empty_like(dx), torch.empty_like(dx)
+    gs = torch.empty(c, dtype=torch.float32, device="cuda")
+    gth = torch.empty_like(gs)
+    out = torch.zeros(3, dtype=torch.float64, device="cuda")
+    t = fq.FqTensor.from_torch(n, c, m, -127, 127, x=dx, y=y, theta=dth, gy=gy, gx=gx, gs=gs, gtheta=gth)
+    d = fq.FqDistill.from_torch(n, c, m, y, dt, out, gy, lam=0.5, upstream=512.0)
+    ws_b = H.workspace_for(t, fq.FQ_MODE_BACKWARD)
+    ws_d = torch.empty(fq.fq_distill_workspace_bytes(d) // 8, dtype=torch.float64, device="cuda")
+    fq.fq_forward(t)
+    fq.fq_distill_loss(d, ws_d)
+    fq.fq_backward(t, ws_b)
+    torch.cuda.synchronize()
+
+    s, active = oracle.scale(theta)
+    ry, _ = oracle.forward(x, s, -127, 127, n, c, m, want_q=False)
+    mse, cosim, loss, rgy = oracle.distill(ry, teacher, 0.5, float(np.float32(1e-8)), 512.0)
+    assert np.array_equal(y.cpu().numpy().view(np.uint16), ry.view(np.uint16))
+    assert abs(out.cpu().numpy()[2] - loss) <= 1e-12 * abs(loss)
+    gy_dist = H.ulp_distance(gy.cpu().numpy(), rgy)
+    assert gy_dist.max() <= 1 and (gy_dist != 0).sum() <= 3
+    # the oracle's backward runs on the oracle's own gy; where the two gy differ by an ulp, gx
+    # (a masked copy of gy) differs by the same ulp and the channel sums move by ~1e-8 relative
+    rb = oracle.backward(x, rgy, s, theta, active, -127, 127, n, c, m)
+    gx_dist = H.ulp_distance(gx.cpu().numpy(), rb["gx"])
+    assert gx_dist.max() <= 1 and (gx_dist != 0).sum() <= (gy_dist != 0).sum()
+    scale_ref = np.maximum(np.abs(rb["gs"]), 1e-5 * rb["aabs"])
+    assert np.all(np.abs(gs.cpu().numpy().astype(np.float64) - rb["gs"]) <= 1e-5 * scale_ref)
