@@ -7,8 +7,9 @@
 // stride is M elements, so the layout is read the way it lies in memory: a wavefront owns 64
 // lanes x V consecutive positions of one image (one coalesced row per channel) and walks over a
 // group of channels, every lane keeping the four sums of its V positions (a.b, a.a, b.b,
-// (a-b)^2) in binary64 registers.  No transposition, no LDS, no atomics:
-//   stats kernel   per (position tile, channel group): partial sums -> workspace
+// (a-b)^2) in binary64 registers.  No transposition, no atomics:
+//   stats kernel   per (position tile, channel group): partial sums, four groups added through
+//                  LDS -> workspace
 //   coef kernel    per position: adds the groups in index order, forms cos and the two
 //                  coefficients of the gradient, and block-reduces cos and the squared error
 //   grad kernel    elementwise: ga = k1 (a - b) - cB b + cA a, rounded once to the I/O type;
@@ -35,16 +36,19 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kUnrollC = 8;            // channels in flight per wavefront (two loads each)
 constexpr unsigned kTargetWaves = 2048;  // eight wavefronts per compute unit
 constexpr unsigned kMaxGroups = 16;
+constexpr long long kMinTiles = 512;      // prefer this many position tiles before narrowing the loads
+constexpr unsigned kMaxSlots = kMaxGroups / kWaves;
 
 struct DistillArgs {
     const void *a, *b;
     void *ga;
-    double *partial;    // [groups][positions][4]
+    double *partial;    // [slots][positions][4]
     double *coef;       // [positions][2]
     double *blocksum;   // [coef blocks][2]
     double *out;        // mse, cosim, loss
     long long M, P;     // positions per image, positions in total
-    unsigned C, groups, per_group, tiles_per_n, tiles, coef_blocks;
+    unsigned C, groups, per_group, slots, tiles_per_n, tiles, coef_blocks;
+                        // slots = ceil(groups / 4): partial sums per position left by the stats kernel
     double k1u, k2u, eps, lambda, inv_ncm, inv_nm;
 };
 
@@ -91,58 +95,97 @@ __device__ __forceinline__ Where locate(const DistillArgs &k, unsigned groups, u
     return w;
 }
 
+// One block = one position tile x up to four consecutive channel groups, one per wavefront.
+// Loads roll: as soon as a channel's pair of vectors has been consumed its registers are
+// refilled with the channel kUnrollC further on, so 2 x kUnrollC loads stay in flight while the
+// binary64 arithmetic runs.  The four wavefronts then add their sums through LDS (fixed order:
+// (w0 + w2) + (w1 + w3)) and the block writes one partial per position.
 template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void distill_stats_kernel(DistillArgs k)
 {
     typedef typename Pack<T, V>::type VT;
-    const Where w = locate<V>(k, k.groups, k.per_group);
-    if (!w.active) return;
-    const T *a = (const T *)k.a + w.first;
-    const T *b = (const T *)k.b + w.first;
-    double dot[V], na[V], nb[V], sq[V];
-#pragma unroll
-    for (int e = 0; e < V; ++e) dot[e] = na[e] = nb[e] = sq[e] = 0.0;
+    constexpr int U = kUnrollC;
+    constexpr int ES = V * 4;                         // sums per lane
+    __shared__ double lds[2][ES][65];                 // rows padded: conflict-free both ways
 
+    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const unsigned tile = blockIdx.x / k.slots, slot = blockIdx.x - tile * k.slots;
+    const unsigned g = slot * kWaves + wave;
+    const unsigned n = tile / k.tiles_per_n, tn = tile - n * k.tiles_per_n;
+    long long m0 = ((long long)tn * 64 + lane) * V;
+    if (m0 >= k.M) m0 = k.M - V;                      // lanes past the end re-read the last vector
+    const unsigned c0 = g < k.groups ? g * k.per_group : k.C;
+    const unsigned c1 = c0 + k.per_group < k.C ? c0 + k.per_group : k.C;
+    const unsigned nch = c1 - c0;                     // 0 for a wavefront without a group
+    const long long first = ((long long)n * k.C + (nch ? c0 : 0u)) * k.M + m0;
+    const T *a = (const T *)k.a + first;
+    const T *b = (const T *)k.b + first;
+
+    double acc[ES];
+#pragma unroll
+    for (int i = 0; i < ES; ++i) acc[i] = 0.0;
     auto accumulate = [&](const VT &va, const VT &vb) {
 #pragma unroll
         for (int e = 0; e < V; ++e) {
             const double x = (double)(float)Pack<T, V>::get(va, e);
             const double y = (double)(float)Pack<T, V>::get(vb, e);
             const double d = x - y;
-            dot[e] = __builtin_fma(x, y, dot[e]);
-            na[e] = __builtin_fma(x, x, na[e]);
-            nb[e] = __builtin_fma(y, y, nb[e]);
-            sq[e] = __builtin_fma(d, d, sq[e]);
+            acc[e * 4 + 0] = __builtin_fma(x, y, acc[e * 4 + 0]);
+            acc[e * 4 + 1] = __builtin_fma(x, x, acc[e * 4 + 1]);
+            acc[e * 4 + 2] = __builtin_fma(y, y, acc[e * 4 + 2]);
+            acc[e * 4 + 3] = __builtin_fma(d, d, acc[e * 4 + 3]);
         }
     };
 
-    unsigned c = w.c0;
-    for (; c + kUnrollC <= w.c1; c += kUnrollC) {
-        VT ra[kUnrollC], rb[kUnrollC];
+    if (nch) {
+        VT ra[U], rb[U];
 #pragma unroll
-        for (int u = 0; u < kUnrollC; ++u) {
-            ra[u] = ld_global((const VT *)(a + (long long)u * k.M));
-            rb[u] = ld_global((const VT *)(b + (long long)u * k.M));
+        for (int u = 0; u < U; ++u) {
+            const unsigned cu = (unsigned)u < nch ? (unsigned)u : nch - 1;
+            ra[u] = ld_global((const VT *)(a + (long long)cu * k.M));
+            rb[u] = ld_global((const VT *)(b + (long long)cu * k.M));
+        }
+        unsigned c = 0;
+        for (; c + U < nch; c += U) {                 // a next block exists, at least in part
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                accumulate(ra[u], rb[u]);
+                unsigned nc = c + U + u;
+                if (nc >= nch) nc = nch - 1;          // re-read of the last channel, never used
+                ra[u] = ld_global((const VT *)(a + (long long)nc * k.M));
+                rb[u] = ld_global((const VT *)(b + (long long)nc * k.M));
+            }
         }
 #pragma unroll
-        for (int u = 0; u < kUnrollC; ++u) accumulate(ra[u], rb[u]);
-        a += (long long)kUnrollC * k.M;
-        b += (long long)kUnrollC * k.M;
+        for (int u = 0; u < U; ++u)
+            if (c + u < nch) accumulate(ra[u], rb[u]);
     }
-    for (; c < w.c1; ++c) {
-        const VT va = ld_global((const VT *)a), vb = ld_global((const VT *)b);
-        accumulate(va, vb);
-        a += k.M;
-        b += k.M;
-    }
-    if (w.valid) {
-        const unsigned g = w.c0 / k.per_group;
-        double4v *dst = (double4v *)k.partial + ((long long)g * k.P + w.p0);
+
+    if (wave >= 2) {
 #pragma unroll
-        for (int e = 0; e < V; ++e) {
-            double4v o = {dot[e], na[e], nb[e], sq[e]};
-            st_global(dst + e, o);
-        }
+        for (int i = 0; i < ES; ++i) lds[wave - 2][i][lane] = acc[i];
+    }
+    __syncthreads();
+    if (wave < 2) {
+#pragma unroll
+        for (int i = 0; i < ES; ++i) acc[i] += lds[wave][i][lane];
+    }
+    __syncthreads();
+    if (wave < 2) {
+#pragma unroll
+        for (int i = 0; i < ES; ++i) lds[wave][i][lane] = acc[i];
+    }
+    __syncthreads();
+    // 64 V positions x 4 sums of this tile, in the order they lie in the workspace
+    double *dst = k.partial + ((long long)slot * k.P + (long long)n * k.M + (long long)tn * 64 * V) * 4;
+    const long long left = (k.M - (long long)tn * 64 * V) * 4;   // doubles of this tile that exist
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        const unsigned idx = threadIdx.x + j * kThreads;
+        const unsigned pp = idx >> 2, stat = idx & 3u;
+        const unsigned src = pp / V, es = (pp % V) * 4 + stat;
+        const double v = lds[0][es][src] + lds[1][es][src];
+        if ((long long)idx < left) st_global(dst + idx, v);
     }
 }
 
@@ -169,12 +212,17 @@ __global__ __launch_bounds__(kThreads) void distill_coef_kernel(DistillArgs k)
     if (p < k.P) {
         double dot = 0.0, na = 0.0, nb = 0.0;
         const double4v *src = (const double4v *)k.partial + p;
-        for (unsigned g = 0; g < k.groups; ++g) {
-            const double4v v = ld_global(src + (long long)g * k.P);
-            dot += v[0];
-            na += v[1];
-            nb += v[2];
-            sq += v[3];
+        double4v v[kMaxSlots];
+#pragma unroll
+        for (unsigned j = 0; j < kMaxSlots; ++j) v[j] = ld_global(src + (long long)(j < k.slots ? j : k.slots - 1) * k.P);
+#pragma unroll
+        for (unsigned j = 0; j < kMaxSlots; ++j) {
+            if (j < k.slots) {
+                dot += v[j][0];
+                na += v[j][1];
+                nb += v[j][2];
+                sq += v[j][3];
+            }
         }
         const double ra = sqrt(na), rb = sqrt(nb);
         // a NaN norm stays NaN, so a non-finite input poisons its whole position visibly
@@ -278,7 +326,7 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Plan {
     int vec;                 // elements per lane
-    unsigned tiles_per_n, tiles, groups, per_group, grad_groups, grad_per_group, coef_blocks;
+    unsigned tiles_per_n, tiles, groups, per_group, slots, grad_groups, grad_per_group, coef_blocks;
     size_t off_coef, off_blocksum, bytes;
 };
 
@@ -319,9 +367,16 @@ fq_status make_plan(const fq_distill *d, Plan &pl)
         return FQ_OK;
     }
     const int full = (int)(kVecBytes / esz);
-    const bool vec_ok = !empty && d->inner % full == 0 && (uintptr_t)d->student % kVecBytes == 0 &&
-                        (uintptr_t)d->teacher % kVecBytes == 0 && (uintptr_t)d->gstudent % kVecBytes == 0;
-    pl.vec = vec_ok ? full : 1;
+    // Elements per lane: the widest load whose tiles (64 lanes x vec positions) are still many
+    // enough to fill the chip without splitting the channels into many groups; a narrow load
+    // still covers whole cache lines (64 lanes x 4 bytes = two lines).
+    const uintptr_t addr_bits = (uintptr_t)d->student | (uintptr_t)d->teacher | (uintptr_t)d->gstudent;
+    pl.vec = 1;
+    for (int v = full; v > 1; v /= 2) {
+        if (d->inner % v || addr_bits % (v * esz)) continue;
+        pl.vec = v;
+        if (d->n * ((d->inner + 64LL * v - 1) / (64LL * v)) >= kMinTiles) break;
+    }
     const long long per_tile = 64LL * pl.vec;
     const long long tpn = empty ? 0 : (d->inner + per_tile - 1) / per_tile;
     if (tpn * d->n > 0x3fffffffLL / kMaxGroups) return FQ_ERR_SHAPE;
@@ -342,7 +397,8 @@ fq_status make_plan(const fq_distill *d, Plan &pl)
         pl.grad_per_group = pl.per_group;
     }
     pl.coef_blocks = (unsigned)((P + kThreads - 1) / kThreads);
-    const size_t partial = align256((size_t)pl.groups * (size_t)P * 4 * sizeof(double));
+    pl.slots = (pl.groups + kWaves - 1) / kWaves;
+    const size_t partial = align256((size_t)pl.slots * (size_t)P * 4 * sizeof(double));
     const size_t coef = align256((size_t)P * 2 * sizeof(double));
     const size_t blocksum = align256((size_t)pl.coef_blocks * 2 * sizeof(double));
     pl.off_coef = partial;
@@ -364,7 +420,7 @@ __global__ void distill_empty_kernel(double *out, bool has_positions)
 template <typename T, int V>
 fq_status launch(const DistillArgs &k, const Plan &pl, bool want_grad, hipStream_t st)
 {
-    const unsigned stats_blocks = (pl.tiles * pl.groups + kWaves - 1) / kWaves;
+    const unsigned stats_blocks = pl.tiles * pl.slots;
     distill_stats_kernel<T, V><<<stats_blocks, kThreads, 0, st>>>(k);
     distill_coef_kernel<<<pl.coef_blocks, kThreads, 0, st>>>(k);
     if (want_grad) {
@@ -414,6 +470,7 @@ fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes,
     k.C = (unsigned)d->channels;
     k.groups = pl.groups;
     k.per_group = pl.per_group;
+    k.slots = pl.slots;
     k.tiles_per_n = pl.tiles_per_n;
     k.tiles = pl.tiles;
     k.coef_blocks = pl.coef_blocks;
@@ -426,9 +483,19 @@ fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes,
     k.inv_ncm = 1.0 / ncm;
     k.inv_nm = 1.0 / nm;
     const bool grad = d->gstudent != nullptr;
-    if (d->dtype == FQ_F16)
-        return pl.vec > 1 ? launch<_Float16, 8>(k, pl, grad, st) : launch<_Float16, 1>(k, pl, grad, st);
-    return pl.vec > 1 ? launch<float, 4>(k, pl, grad, st) : launch<float, 1>(k, pl, grad, st);
+    if (d->dtype == FQ_F16) {
+        switch (pl.vec) {
+        case 8: return launch<_Float16, 8>(k, pl, grad, st);
+        case 4: return launch<_Float16, 4>(k, pl, grad, st);
+        case 2: return launch<_Float16, 2>(k, pl, grad, st);
+        default: return launch<_Float16, 1>(k, pl, grad, st);
+        }
+    }
+    switch (pl.vec) {
+    case 4: return launch<float, 4>(k, pl, grad, st);
+    case 2: return launch<float, 2>(k, pl, grad, st);
+    default: return launch<float, 1>(k, pl, grad, st);
+    }
 }
 
 }  // extern "C"
