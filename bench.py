@@ -49,7 +49,7 @@ WORKLOAD_TEXT = {
 
 def distill_bench(args, cases, fq, torch, np):
     """--pass distill: fq_distill_loss (loss and gradient with respect to the student) on one
-    student/teacher pair shaped like the workload's tensor.  A step is one call (three kernels).
+    student/teacher pair shaped like the workload's tensor.  A step is one call (two kernels).
     Algorithmic bytes per element: read student, read teacher, write the gradient = 3 b; the
     second read of the pair by the gradient kernel and the per-position statistics are the
     implementation's own traffic and are not counted."""
@@ -102,7 +102,7 @@ def distill_bench(args, cases, fq, torch, np):
     step_bytes = 3 * io_bytes
     value = step_bytes / sec_per_step / 1e9
     achieved = step_bytes / gpu_sec_per_step / 1e9
-    roofline = {"bound": "hbm", "kernel": "fq_distill_loss: stats + coef + grad kernels of one call",
+    roofline = {"bound": "hbm", "kernel": "fq_distill_loss: distill_stats_kernel + distill_grad_kernel of one call",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "bytes_per_launch": step_bytes, "avg_us": round(gpu_sec_per_step * 1e6, 2),
@@ -135,7 +135,7 @@ def distill_bench(args, cases, fq, torch, np):
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload] + ", as one student/teacher pair [n, channels, "
                                "h*w]: loss of Eq. (7) and its gradient",
-                   "launches_per_step": 3, "elements": cs.numel, "bytes_per_step": step_bytes,
+                   "launches_per_step": 2, "elements": cs.numel, "bytes_per_step": step_bytes,
                    "ring_buffer_sets": int(ring), "workspace_bytes": ws_bytes},
         "host_enqueue_us_per_step": round((t_enq - t0) / args.steps * 1e6, 2),
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),

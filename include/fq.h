@@ -195,7 +195,7 @@ void fq_plan_destroy(fq_plan *plan);
  * gstudent = upstream * dloss/dstudent in the tensors' dtype (rounded once from binary64; a
  * clamped norm counts as a constant).  `upstream` is the factor in front of this pair's loss in
  * the total (Eq. (7) sums the pairs: 1, or the loss scale of an FP16 run).  student / teacher are
- * contiguous [n, channels, inner]; gstudent may be exactly student or teacher (in place).  Three
+ * contiguous [n, channels, inner]; gstudent may be exactly student or teacher (in place).  Two
  * launches; no atomics, fixed summation order.  A tensor without elements needs no workspace and
  * gives NaN for mse and loss (a mean of nothing); cosim is then NaN without positions and 0 with
  * positions but no channels.  The workspace need not be initialised and may be shared with other calls

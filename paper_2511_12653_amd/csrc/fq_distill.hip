@@ -8,10 +8,10 @@
 // lanes x V consecutive positions of one image (one coalesced row per channel) and walks over a
 // group of channels, every lane keeping the four sums of its V positions (a.b, a.a, b.b,
 // (a-b)^2) in binary64 registers.  No transposition, no atomics:
-//   stats kernel   per (position tile, channel group): partial sums, four groups added through
-//                  LDS -> workspace
-//   coef kernel    per position: adds the groups in index order, forms cos and the two
-//                  coefficients of the gradient, and block-reduces cos and the squared error
+//   stats kernel   one block per position tile, one wavefront per channel group (up to 16); the
+//                  wavefronts add their sums through LDS in a fixed tree, then the block forms
+//                  cos and the two coefficients of the gradient for its positions and leaves
+//                  its sums of cos and of the squared error
 //   grad kernel    elementwise: ga = k1 (a - b) - cB b + cA a, rounded once to the I/O type;
 //                  its first wavefront also adds the block sums in index order into the 3 results
 // All arithmetic is binary64 (two conversions and five fused multiply-adds per element pair, well
@@ -31,24 +31,23 @@ using namespace dev;
 
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 256;             // gradient kernel
 constexpr int kWaves = kThreads / 64;
-constexpr int kUnrollC = 8;            // channels in flight per wavefront (two loads each)
-constexpr unsigned kTargetWaves = 2048;  // eight wavefronts per compute unit
-constexpr unsigned kMaxGroups = 16;
-constexpr long long kMinTiles = 512;      // prefer this many position tiles before narrowing the loads
-constexpr unsigned kMaxSlots = kMaxGroups / kWaves;
+constexpr int kUnrollC = 8;               // channels in flight per wavefront (two loads each)
+constexpr unsigned kTargetWaves = 2048;   // eight wavefronts per compute unit
+constexpr unsigned kMaxGroups = 16;       // wavefronts of a statistics block (1024 threads)
+constexpr unsigned kTreeSlots = 4;        // wavefronts that hand their sums over per round of the LDS tree
+constexpr int kMaxVec = 4;                // positions per lane (a 1024-thread block has 128 VGPRs per lane)
+constexpr long long kMinTiles = 256;      // prefer this many position tiles before narrowing the loads
 
 struct DistillArgs {
     const void *a, *b;
     void *ga;
-    double *partial;    // [slots][positions][4]
     double *coef;       // [positions][2]
-    double *blocksum;   // [coef blocks][2]
+    double *blocksum;   // [tiles][2]: per-block sums of cos and of (a-b)^2
     double *out;        // mse, cosim, loss
     long long M, P;     // positions per image, positions in total
-    unsigned C, groups, per_group, slots, tiles_per_n, tiles, coef_blocks;
-                        // slots = ceil(groups / 4): partial sums per position left by the stats kernel
+    unsigned C, groups, per_group, tiles_per_n, tiles;
     double k1u, k2u, eps, lambda, inv_ncm, inv_nm;
 };
 
@@ -95,26 +94,48 @@ __device__ __forceinline__ Where locate(const DistillArgs &k, unsigned groups, u
     return w;
 }
 
-// One block = one position tile x up to four consecutive channel groups, one per wavefront.
-// Loads roll: as soon as a channel's pair of vectors has been consumed its registers are
-// refilled with the channel kUnrollC further on, so 2 x kUnrollC loads stay in flight while the
-// binary64 arithmetic runs.  The four wavefronts then add their sums through LDS (fixed order:
-// (w0 + w2) + (w1 + w3)) and the block writes one partial per position.
+// Sums of `u` and `v` over the block (any number of wavefronts up to 16) in a fixed order; valid
+// in thread 0.  red: 32 doubles of LDS.
+__device__ __forceinline__ void block_sum2(double &u, double &v, double *red)
+{
+    u = wave_sum(u);
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == kSumLane) {
+        red[threadIdx.x >> 6] = u;
+        red[16 + (threadIdx.x >> 6)] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned waves = blockDim.x >> 6;
+        u = v = 0.0;
+        for (unsigned i = 0; i < waves; ++i) {
+            u += red[i];
+            v += red[16 + i];
+        }
+    }
+}
+
+// One block = one position tile; wavefront w takes channel group w.  Loads roll: as soon as a
+// channel's pair of vectors has been consumed its registers are refilled with the channel
+// kUnrollC further on, so 2 x kUnrollC loads stay in flight while the binary64 arithmetic runs.
+// Dynamic LDS: min(kTreeSlots, max(1, p/2)) x 4V x 64 doubles, p = the number of wavefronts
+// rounded up to a power of two.
 template <typename T, int V>
-__global__ __launch_bounds__(kThreads) void distill_stats_kernel(DistillArgs k)
+__global__ __launch_bounds__(1024) void distill_stats_kernel(DistillArgs k)
 {
     typedef typename Pack<T, V>::type VT;
-    constexpr int U = kUnrollC;
+    constexpr int U = V >= 4 ? kUnrollC : 2 * kUnrollC;   // narrow loads: more of them in flight
     constexpr int ES = V * 4;                         // sums per lane
-    __shared__ double lds[2][ES][65];                 // rows padded: conflict-free both ways
+    extern __shared__ double lds[];                   // [slot][ES][64]
+    __shared__ double red[32];
 
-    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const unsigned tile = blockIdx.x / k.slots, slot = blockIdx.x - tile * k.slots;
-    const unsigned g = slot * kWaves + wave;
+    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63, waves = blockDim.x >> 6;
+    const unsigned tile = blockIdx.x;
     const unsigned n = tile / k.tiles_per_n, tn = tile - n * k.tiles_per_n;
-    long long m0 = ((long long)tn * 64 + lane) * V;
+    const long long tile_m = (long long)tn * 64 * V;  // first position of the tile in its image
+    long long m0 = tile_m + (long long)lane * V;
     if (m0 >= k.M) m0 = k.M - V;                      // lanes past the end re-read the last vector
-    const unsigned c0 = g < k.groups ? g * k.per_group : k.C;
+    const unsigned c0 = wave * k.per_group < k.C ? wave * k.per_group : k.C;
     const unsigned c1 = c0 + k.per_group < k.C ? c0 + k.per_group : k.C;
     const unsigned nch = c1 - c0;                     // 0 for a wavefront without a group
     const long long first = ((long long)n * k.C + (nch ? c0 : 0u)) * k.M + m0;
@@ -161,85 +182,56 @@ __global__ __launch_bounds__(kThreads) void distill_stats_kernel(DistillArgs k)
             if (c + u < nch) accumulate(ra[u], rb[u]);
     }
 
-    if (wave >= 2) {
+    // Fixed tree over the wavefronts: w += w + stride for stride = 8, 4, 2, 1, at most kTreeSlots
+    // wavefronts handing over per round so that the LDS footprint stays at 4 x 4V x 64 doubles.
+    for (unsigned stride = kMaxGroups / 2; stride >= 1; stride >>= 1) {
+        if (stride >= waves) continue;                // uniform over the block
+        for (unsigned base = 0; base < stride; base += kTreeSlots) {
+            const unsigned giver = stride + base;     // first wavefront that hands over in this round
+            if (wave >= giver && wave < giver + kTreeSlots && wave < 2 * stride) {
 #pragma unroll
-        for (int i = 0; i < ES; ++i) lds[wave - 2][i][lane] = acc[i];
-    }
-    __syncthreads();
-    if (wave < 2) {
-#pragma unroll
-        for (int i = 0; i < ES; ++i) acc[i] += lds[wave][i][lane];
-    }
-    __syncthreads();
-    if (wave < 2) {
-#pragma unroll
-        for (int i = 0; i < ES; ++i) lds[wave][i][lane] = acc[i];
-    }
-    __syncthreads();
-    // 64 V positions x 4 sums of this tile, in the order they lie in the workspace
-    double *dst = k.partial + ((long long)slot * k.P + (long long)n * k.M + (long long)tn * 64 * V) * 4;
-    const long long left = (k.M - (long long)tn * 64 * V) * 4;   // doubles of this tile that exist
-#pragma unroll
-    for (int j = 0; j < V; ++j) {
-        const unsigned idx = threadIdx.x + j * kThreads;
-        const unsigned pp = idx >> 2, stat = idx & 3u;
-        const unsigned src = pp / V, es = (pp % V) * 4 + stat;
-        const double v = lds[0][es][src] + lds[1][es][src];
-        if ((long long)idx < left) st_global(dst + idx, v);
-    }
-}
-
-// Sum of `v` over the block in a fixed order; valid in thread 0.
-__device__ __forceinline__ double block_sum(double v, double *lds)
-{
-    v = wave_sum(v);
-    if ((threadIdx.x & 63) == kSumLane) lds[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double total = 0.0;
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int i = 0; i < kWaves; ++i) total += lds[i];
-    }
-    __syncthreads();
-    return total;
-}
-
-__global__ __launch_bounds__(kThreads) void distill_coef_kernel(DistillArgs k)
-{
-    __shared__ double lds[kWaves];
-    const long long p = (long long)blockIdx.x * kThreads + threadIdx.x;
-    double cosp = 0.0, sq = 0.0;
-    if (p < k.P) {
-        double dot = 0.0, na = 0.0, nb = 0.0;
-        const double4v *src = (const double4v *)k.partial + p;
-        double4v v[kMaxSlots];
-#pragma unroll
-        for (unsigned j = 0; j < kMaxSlots; ++j) v[j] = ld_global(src + (long long)(j < k.slots ? j : k.slots - 1) * k.P);
-#pragma unroll
-        for (unsigned j = 0; j < kMaxSlots; ++j) {
-            if (j < k.slots) {
-                dot += v[j][0];
-                na += v[j][1];
-                nb += v[j][2];
-                sq += v[j][3];
+                for (int i = 0; i < ES; ++i) lds[((wave - giver) * ES + i) * 64 + lane] = acc[i];
             }
-        }
-        const double ra = sqrt(na), rb = sqrt(nb);
-        // a NaN norm stays NaN, so a non-finite input poisons its whole position visibly
-        const double ca = ra < k.eps ? k.eps : ra, cb = rb < k.eps ? k.eps : rb;
-        const double inv = 1.0 / (ca * cb);
-        cosp = dot / (ca * cb);
-        const double self = ra > k.eps ? cosp / na : 0.0;
-        if (k.coef) {
-            double2v o = {k.k2u * inv, k.k2u * self};
-            st_global((double2v *)k.coef + p, o);
+            __syncthreads();
+            if (wave >= base && wave < base + kTreeSlots && wave < stride && wave + stride < waves) {
+#pragma unroll
+                for (int i = 0; i < ES; ++i) acc[i] += lds[((wave - base) * ES + i) * 64 + lane];
+            }
+            __syncthreads();
         }
     }
-    const double sc = block_sum(cosp, lds);
-    const double ss = block_sum(sq, lds);
+    if (wave == 0) {
+#pragma unroll
+        for (int i = 0; i < ES; ++i) lds[i * 64 + lane] = acc[i];
+    }
+    __syncthreads();
+
+    // One thread per position of the tile: cos, the coefficients of the gradient, block sums.
+    double cos_sum = 0.0, sq_sum = 0.0;
+    for (unsigned pp = threadIdx.x; pp < 64u * V; pp += blockDim.x) {
+        const unsigned src = pp / V, e = pp % V;
+        const long long m = tile_m + pp;
+        if (m < k.M) {
+            const double dot = lds[(e * 4 + 0) * 64 + src], na = lds[(e * 4 + 1) * 64 + src];
+            const double nb = lds[(e * 4 + 2) * 64 + src], sq = lds[(e * 4 + 3) * 64 + src];
+            const double ra = sqrt(na), rb = sqrt(nb);
+            // a NaN norm stays NaN, so a non-finite input poisons its whole position visibly
+            const double ca = ra < k.eps ? k.eps : ra, cb = rb < k.eps ? k.eps : rb;
+            const double inv = 1.0 / (ca * cb);
+            const double cosp = dot / (ca * cb);
+            const double self = ra > k.eps ? cosp / na : 0.0;
+            if (k.coef) {
+                double2v o = {k.k2u * inv, k.k2u * self};
+                st_global((double2v *)k.coef + ((long long)n * k.M + m), o);
+            }
+            cos_sum += cosp;
+            sq_sum += sq;
+        }
+    }
+    block_sum2(cos_sum, sq_sum, red);
     if (threadIdx.x == 0) {
-        double2v o = {sc, ss};
-        st_global((double2v *)k.blocksum + blockIdx.x, o);
+        double2v o = {cos_sum, sq_sum};
+        st_global((double2v *)k.blocksum + tile, o);
     }
 }
 
@@ -248,7 +240,7 @@ __device__ __forceinline__ void finish(const DistillArgs &k)
 {
     const unsigned lane = threadIdx.x & 63;
     double sc = 0.0, ss = 0.0;
-    for (unsigned i = lane; i < k.coef_blocks; i += 64) {
+    for (unsigned i = lane; i < k.tiles; i += 64) {
         const double2v v = ld_global((const double2v *)k.blocksum + i);
         sc += v[0];
         ss += v[1];
@@ -326,8 +318,8 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Plan {
     int vec;                 // elements per lane
-    unsigned tiles_per_n, tiles, groups, per_group, slots, grad_groups, grad_per_group, coef_blocks;
-    size_t off_coef, off_blocksum, bytes;
+    unsigned tiles_per_n, tiles, groups, per_group, grad_groups, grad_per_group;
+    size_t stats_lds, off_blocksum, bytes;
 };
 
 fq_status make_plan(const fq_distill *d, Plan &pl)
@@ -366,7 +358,7 @@ fq_status make_plan(const fq_distill *d, Plan &pl)
         pl.bytes = 256;
         return FQ_OK;
     }
-    const int full = (int)(kVecBytes / esz);
+    const int full = (int)(kVecBytes / esz) < kMaxVec ? (int)(kVecBytes / esz) : kMaxVec;
     // Elements per lane: the widest load whose tiles (64 lanes x vec positions) are still many
     // enough to fill the chip without splitting the channels into many groups; a narrow load
     // still covers whole cache lines (64 lanes x 4 bytes = two lines).
@@ -379,7 +371,7 @@ fq_status make_plan(const fq_distill *d, Plan &pl)
     }
     const long long per_tile = 64LL * pl.vec;
     const long long tpn = empty ? 0 : (d->inner + per_tile - 1) / per_tile;
-    if (tpn * d->n > 0x3fffffffLL / kMaxGroups) return FQ_ERR_SHAPE;
+    if (tpn * d->n > 0x3fffffffLL) return FQ_ERR_SHAPE;
     pl.tiles_per_n = (unsigned)tpn;
     pl.tiles = (unsigned)(tpn * d->n);
     auto split = [&](unsigned want_waves, unsigned cap, unsigned &groups, unsigned &per_group) {
@@ -396,14 +388,15 @@ fq_status make_plan(const fq_distill *d, Plan &pl)
         pl.grad_groups = pl.groups;
         pl.grad_per_group = pl.per_group;
     }
-    pl.coef_blocks = (unsigned)((P + kThreads - 1) / kThreads);
-    pl.slots = (pl.groups + kWaves - 1) / kWaves;
-    const size_t partial = align256((size_t)pl.slots * (size_t)P * 4 * sizeof(double));
+    unsigned pow2 = 1;
+    while (pow2 < pl.groups) pow2 *= 2;
+    unsigned slots = pow2 > 1 ? pow2 / 2 : 1;
+    if (slots > kTreeSlots) slots = kTreeSlots;
+    pl.stats_lds = (size_t)slots * 4 * pl.vec * 64 * sizeof(double);
     const size_t coef = align256((size_t)P * 2 * sizeof(double));
-    const size_t blocksum = align256((size_t)pl.coef_blocks * 2 * sizeof(double));
-    pl.off_coef = partial;
-    pl.off_blocksum = partial + coef;
-    pl.bytes = partial + coef + blocksum;
+    const size_t blocksum = align256((size_t)pl.tiles * 2 * sizeof(double));
+    pl.off_blocksum = coef;
+    pl.bytes = coef + blocksum;
     if (pl.bytes < 256) pl.bytes = 256;
     return FQ_OK;
 }
@@ -420,9 +413,7 @@ __global__ void distill_empty_kernel(double *out, bool has_positions)
 template <typename T, int V>
 fq_status launch(const DistillArgs &k, const Plan &pl, bool want_grad, hipStream_t st)
 {
-    const unsigned stats_blocks = pl.tiles * pl.slots;
-    distill_stats_kernel<T, V><<<stats_blocks, kThreads, 0, st>>>(k);
-    distill_coef_kernel<<<pl.coef_blocks, kThreads, 0, st>>>(k);
+    distill_stats_kernel<T, V><<<pl.tiles, 64 * pl.groups, pl.stats_lds, st>>>(k);
     if (want_grad) {
         const unsigned grad_blocks = (pl.tiles * pl.grad_groups + kWaves - 1) / kWaves;
         distill_grad_kernel<T, V><<<grad_blocks, kThreads, 0, st>>>(k, pl.grad_groups, pl.grad_per_group);
@@ -461,8 +452,7 @@ fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes,
     k.a = d->student;
     k.b = d->teacher;
     k.ga = d->gstudent;
-    k.partial = (double *)workspace;
-    k.coef = d->gstudent ? (double *)((char *)workspace + pl.off_coef) : nullptr;
+    k.coef = d->gstudent ? (double *)workspace : nullptr;
     k.blocksum = (double *)((char *)workspace + pl.off_blocksum);
     k.out = d->out;
     k.M = d->inner;
@@ -470,10 +460,8 @@ fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes,
     k.C = (unsigned)d->channels;
     k.groups = pl.groups;
     k.per_group = pl.per_group;
-    k.slots = pl.slots;
     k.tiles_per_n = pl.tiles_per_n;
     k.tiles = pl.tiles;
-    k.coef_blocks = pl.coef_blocks;
     const double ncm = (double)d->n * (double)d->channels * (double)d->inner;
     const double nm = (double)d->n * (double)d->inner;
     k.k1u = (double)d->upstream * (2.0 / ncm);
@@ -485,7 +473,6 @@ fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes,
     const bool grad = d->gstudent != nullptr;
     if (d->dtype == FQ_F16) {
         switch (pl.vec) {
-        case 8: return launch<_Float16, 8>(k, pl, grad, st);
         case 4: return launch<_Float16, 4>(k, pl, grad, st);
         case 2: return launch<_Float16, 2>(k, pl, grad, st);
         default: return launch<_Float16, 1>(k, pl, grad, st);

@@ -140,17 +140,17 @@ def _distill(fq, **kw):
 
 def test_distill_struct_and_workspace(fq):
     assert ctypes.sizeof(fq.FqDistill) == 3 * 8 + 4 * 4 + 4 * 8
-    # one image of 19200 positions: 38 tiles of 512 positions -> capped at 16 channel groups,
-    # four of which share a block and leave one partial
+    # coefficients (2 doubles per position) + per-tile sums (2 doubles per tile of 64 x 2 positions:
+    # one image of 19200 positions is cut into 150 tiles of 128 positions)
     P = 19200
-    want = 4 * P * 32 + P * 16 + ((P + 255) // 256) * 16
+    want = P * 16 + 150 * 16
     got = fq.fq_distill_workspace_bytes(_distill(fq))
-    assert got % 256 == 0 and want <= got < want + 3 * 256
-    # a batch of 15 images: 570 tiles -> 4 groups -> 1 partial
+    assert got % 256 == 0 and want <= got < want + 2 * 256
+    # a batch of 15 images: 15 * 75 tiles of 256 positions
     P = 15 * 19200
-    want = 1 * P * 32 + P * 16 + ((P + 255) // 256) * 16
+    want = P * 16 + 15 * 75 * 16
     got = fq.fq_distill_workspace_bytes(_distill(fq, n=15))
-    assert want <= got < want + 3 * 256
+    assert want <= got < want + 2 * 256
     # empty tensors validate and need only the minimum
     assert fq.fq_distill_workspace_bytes(_distill(fq, n=0)) == 256
     assert fq.fq_distill_workspace_bytes(_distill(fq, channels=0, student=None, teacher=None)) == 256
