@@ -106,6 +106,21 @@ def test_scalar_path(oracle, dtype, shape, misalign):
     _run(a, b, 1.0, oracle, misalign=misalign, label="scalar")
 
 
+def test_random_shapes(oracle):
+    """Thirty seeded shapes across the planner's cases: one to thousands of tiles, channel counts
+    below and above the number of wavefronts of a block, every lane width, ragged tails."""
+    rng = np.random.Generator(np.random.Philox(2024))
+    for i in range(30):
+        n = int(rng.choice([1, 1, 2, 3, 7, 40]))
+        c = int(rng.choice([1, 2, 3, 5, 15, 16, 17, 33, 100, 257, 1200]))
+        m = int(rng.choice([1, 2, 3, 4, 6, 64, 127, 128, 130, 256, 258, 1000, 1028, 4099]))
+        while n * c * m > 6_000_000:
+            m = max(1, m // 2)
+        dtype = np.float16 if rng.integers(0, 2) else np.float32
+        a, b = _pair(100 + i, (n, c, m), dtype)
+        _run(a, b, float(rng.uniform(0.0, 2.0)), oracle, label="random[%d]" % i)
+
+
 @pytest.mark.parametrize("inplace", ["student", "teacher"])
 def test_in_place(oracle, inplace):
     a, b = _pair(13, (2, 40, 520), np.float16)
