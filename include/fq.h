@@ -48,7 +48,8 @@ typedef enum fq_status {
     FQ_ERR_WORKSPACE = -6,     /* workspace NULL or smaller than fq_workspace_bytes() */
     FQ_ERR_SCALE_PARAMS = -7,  /* need finite eps, 0 < s_min <= s_max, no NaN */
     FQ_ERR_LAUNCH = -8,        /* the HIP runtime reported an error while enqueuing */
-    FQ_ERR_ALIAS = -9,         /* output partially overlaps its input (exact in-place is allowed) */
+    FQ_ERR_ALIAS = -9,         /* output partially overlaps its input (exact in-place is allowed; q may not
+                                  overlap x or y at all) */
     FQ_ERR_OPTIMIZER = -10     /* bad fq_adam: step < 1, beta outside [0,1), lr/eps not finite or eps < 0 */
 } fq_status;
 

@@ -30,6 +30,14 @@ bool partial_overlap(const void *a, const void *b, size_t bytes)
     return pa < pb ? (pb - pa) < bytes : (pa - pb) < bytes;
 }
 
+// Any overlap of [a, a+abytes) and [b, b+bbytes).
+bool overlap(const void *a, size_t abytes, const void *b, size_t bbytes)
+{
+    if (!a || !b || abytes == 0 || bbytes == 0) return false;
+    uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
+    return pa < pb + bbytes && pb < pa + abytes;
+}
+
 struct Plan {
     long long numel = 0;
     unsigned slabs = 0, cps = 0, chunk = 0;
@@ -103,6 +111,9 @@ fq_status validate_one(const fq_tensor &t, int mode, Plan &p)
         if (!aligned(t.y, esz)) return FQ_ERR_ALIGN;
         if (t.q && (t.qmin < -128 || t.qmax > 127)) return FQ_ERR_QRANGE;
         if (partial_overlap(t.x, t.y, bytes)) return FQ_ERR_ALIAS;
+        // the codes are a different size per element: they may not share memory with x or y at all
+        if (overlap(t.q, (size_t)p.numel, t.x, bytes) || overlap(t.q, (size_t)p.numel, t.y, bytes))
+            return FQ_ERR_ALIAS;
     } else {
         const bool need_gx = !(t.flags & FQ_FLAG_NO_DX);
         if (p.numel > 0 && (!t.gy || (need_gx && !t.gx))) return FQ_ERR_NULL;
@@ -337,17 +348,33 @@ int copy_table_async(void *dst_device, const void *src_host, size_t bytes, void 
 
 extern "C" {
 
+// Host containers may throw std::bad_alloc for absurd n; nothing may leave through the C ABI.
+#define FQ_GUARDED(expr, on_throw) \
+    try {                          \
+        return (expr);             \
+    } catch (...) {                \
+        return (on_throw);         \
+    }
+
 size_t fq_workspace_bytes(const fq_tensor *ts, int n, int mode)
 {
-    fq::Layout L;
-    if (fq::make_layout(ts, n, mode, L) != FQ_OK) return 0;
-    return L.total;
+    try {
+        fq::Layout L;
+        if (fq::make_layout(ts, n, mode, L) != FQ_OK) return 0;
+        return L.total;
+    } catch (...) {
+        return 0;
+    }
 }
 
 fq_status fq_validate(const fq_tensor *ts, int n, int mode)
 {
-    fq::Layout L;
-    return fq::make_layout(ts, n, mode, L);
+    try {
+        fq::Layout L;
+        return fq::make_layout(ts, n, mode, L);
+    } catch (...) {
+        return FQ_ERR_SHAPE;
+    }
 }
 
 fq_status fq_workspace_init(void *workspace, size_t ws_bytes, void *hip_stream)
@@ -360,19 +387,19 @@ fq_status fq_workspace_init(void *workspace, size_t ws_bytes, void *hip_stream)
 fq_status fq_forward(const fq_tensor *t, void *hip_stream)
 {
     if (!t) return FQ_ERR_NULL;
-    return fq::run(t, 1, FQ_MODE_FORWARD, false, nullptr, 0, hip_stream);
+    FQ_GUARDED(fq::run(t, 1, FQ_MODE_FORWARD, false, nullptr, 0, hip_stream), FQ_ERR_LAUNCH)
 }
 
 fq_status fq_backward(const fq_tensor *t, void *workspace, size_t ws_bytes, void *hip_stream)
 {
     if (!t) return FQ_ERR_NULL;
-    return fq::run(t, 1, FQ_MODE_BACKWARD, false, workspace, ws_bytes, hip_stream);
+    FQ_GUARDED(fq::run(t, 1, FQ_MODE_BACKWARD, false, workspace, ws_bytes, hip_stream), FQ_ERR_LAUNCH)
 }
 
 fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,
                           void *hip_stream)
 {
-    return fq::run(ts, n, mode, true, workspace, ws_bytes, hip_stream);
+    FQ_GUARDED(fq::run(ts, n, mode, true, workspace, ws_bytes, hip_stream), FQ_ERR_LAUNCH)
 }
 
 struct fq_plan {
@@ -383,6 +410,30 @@ struct fq_plan {
     int64_t step = 0;                      // Adam step the device table currently holds
 };
 
+static fq_status fill_plan(fq_plan *p, const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,
+                           void *hip_stream)
+{
+    fq_status st = fq::prepare(ts, n, mode, true, workspace, ws_bytes, hip_stream, p->prepared);
+    if (st != FQ_OK) return st;
+    p->workspace = workspace;
+    p->beta1.resize((size_t)n); p->beta2.resize((size_t)n); p->has_adam.resize((size_t)n);
+    bool first = true;
+    for (int i = 0; i < n; ++i) {
+        const bool on = mode == FQ_MODE_BACKWARD && ts[i].adam && ts[i].channels > 0;
+        p->has_adam[(size_t)i] = on ? 1 : 0;
+        if (on) {
+            p->beta1[(size_t)i] = ts[i].adam->beta1;
+            p->beta2[(size_t)i] = ts[i].adam->beta2;
+            // descriptors created at different steps: no single step is in place, so the first
+            // fq_plan_run_adam refreshes every tensor
+            if (first) p->step = ts[i].adam->step;
+            else if (p->step != ts[i].adam->step) p->step = 0;
+            first = false;
+        }
+    }
+    return FQ_OK;
+}
+
 fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,
                          void *hip_stream, fq_plan **plan)
 {
@@ -390,21 +441,15 @@ fq_status fq_plan_create(const fq_tensor *ts, int n, int mode, void *workspace, 
     *plan = nullptr;
     fq_plan *p = new (std::nothrow) fq_plan();
     if (!p) return FQ_ERR_LAUNCH;
-    fq_status st = fq::prepare(ts, n, mode, true, workspace, ws_bytes, hip_stream, p->prepared);
+    fq_status st;
+    try {
+        st = fill_plan(p, ts, n, mode, workspace, ws_bytes, hip_stream);
+    } catch (...) {
+        st = FQ_ERR_LAUNCH;
+    }
     if (st != FQ_OK) {
         delete p;
         return st;
-    }
-    p->workspace = workspace;
-    p->beta1.resize((size_t)n); p->beta2.resize((size_t)n); p->has_adam.resize((size_t)n);
-    for (int i = 0; i < n; ++i) {
-        const bool on = mode == FQ_MODE_BACKWARD && ts[i].adam && ts[i].channels > 0;
-        p->has_adam[(size_t)i] = on ? 1 : 0;
-        if (on) {
-            p->beta1[(size_t)i] = ts[i].adam->beta1;
-            p->beta2[(size_t)i] = ts[i].adam->beta2;
-            p->step = ts[i].adam->step;
-        }
     }
     *plan = p;
     return FQ_OK;
@@ -420,6 +465,7 @@ fq_status fq_plan_run_adam(fq_plan *plan, int64_t step, void *hip_stream)
 {
     if (!plan) return FQ_ERR_NULL;
     if (step < 1) return FQ_ERR_OPTIMIZER;
+    // (no container grows here: the table and the per-tensor vectors keep their size)
     if (step != plan->step) {
         bool any = false;
         std::vector<fq::DevTensor> &table = plan->prepared.table;

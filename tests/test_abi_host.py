@@ -181,3 +181,11 @@ def test_distill_workspace_errors_before_any_launch(fq):
     # in place over the student or the teacher is accepted
     assert fq.fq_distill_workspace_bytes(_distill(fq, gstudent=0x10000000)) == need
     assert fq.fq_distill_workspace_bytes(_distill(fq, gstudent=0x20000000)) == need
+
+
+def test_codes_may_not_share_memory_with_x_or_y(fq):
+    # the int8 codes are one byte per element; overlapping x (or y) in any way is refused
+    for kw in (dict(q=0x1000), dict(q=0x1000 + 100), dict(q=0x2000 + 8)):
+        d = _desc(fq, x=0x1000, y=0x2000, **kw)
+        assert fq.fq_validate(d, fq.FQ_MODE_FORWARD) == -9
+    assert fq.fq_validate(_desc(fq, x=0x1000, y=0x2000, q=0x3000), fq.FQ_MODE_FORWARD) == 0
