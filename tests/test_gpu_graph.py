@@ -91,3 +91,56 @@ def test_plan_run_in_a_graph():
     finally:
         fq.fq_plan_destroy(plan_f)
         fq.fq_plan_destroy(plan_b)
+
+
+def test_distillation_step_in_a_graph():
+    """forward -> distillation loss and gradient -> backward, captured once and replayed with new
+    data at the same addresses; every replay equals the eager chain bit for bit."""
+    rng = np.random.Generator(np.random.Philox(31))
+    n, c, m = 2, 20, 1536
+    H.say("graph capture: fq_forward + fq_distill_loss + fq_backward, shape (%d, %d, %d)" % (n, c, m))
+    x = torch.from_numpy((rng.standard_normal((n, c, m)) * 1.3).astype(np.float16)).cuda()
+    teacher = torch.from_numpy((rng.standard_normal((n, c, m)) * 1.3).astype(np.float16)).cuda()
+    theta = torch.from_numpy(workloads.theta_for_scale(rng.uniform(0.01, 0.05, c))).cuda()
+    y, gy, gx = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+    gs, gth = torch.empty(c, device="cuda"), torch.empty(c, device="cuda")
+    out = torch.zeros(3, dtype=torch.float64, device="cuda")
+    t = fq.FqTensor.from_torch(n, c, m, -127, 127, x=x, y=y, theta=theta, gy=gy, gx=gx, gs=gs, gtheta=gth)
+    d = fq.FqDistill.from_torch(n, c, m, y, teacher, out, gy, lam=0.5, upstream=256.0)
+    ws_b = H.workspace_for(t, fq.FQ_MODE_BACKWARD)
+    ws_d = torch.empty(fq.fq_distill_workspace_bytes(d) // 8, dtype=torch.float64, device="cuda")
+
+    def chain():
+        fq.fq_forward(t)
+        fq.fq_distill_loss(d, ws_d)
+        fq.fq_backward(t, ws_b)
+
+    def snapshot():
+        return [v.clone() for v in (y, gy, gx, gs, gth, out)]
+
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    chain()                                           # warm up outside the capture
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            chain()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        x.mul_(1.0 + 0.125 * rep)                     # new data, same addresses
+        teacher.add_(0.01 * rep)
+        torch.cuda.synchronize()
+        chain()
+        torch.cuda.synchronize()
+        eager = snapshot()
+        for v in (y, gy, gx):
+            v.zero_()
+        for v in (gs, gth, out):
+            v.fill_(float("nan"))
+        ws_d.fill_(float("nan"))                      # the distillation workspace carries no state
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(snapshot(), eager):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), "replay %d differs" % rep
+    assert torch.isfinite(out).all() and float(out[0]) > 0.0
