@@ -67,3 +67,55 @@ def test_scale_only_training_reduces_quantization_error():
     # the learned scales moved toward each other: clipped channels grew, coarse channels shrank
     s_end, _ = fq_oracle.scale(gpu_theta[-1])
     assert np.all(s_end[0::2] > s0[0::2]) and np.all(s_end[1::2] < s0[1::2])
+
+
+def test_distillation_training_loop_all_in_library_kernels():
+    """The scale-only QAT step of Sec. 3.1-3.2 with the loss of Eq. (7): FQ forward of the student
+    features, distillation loss and gradient against the unquantized teacher, STE backward with the
+    fused Adam step.  No torch arithmetic anywhere in the GPU loop; the oracle runs the same loop."""
+    rng = np.random.default_rng(21)
+    n_img, c, m, steps, lam, up = 2, 8, 2048, 30, 0.5, 1024.0
+    sigma = rng.uniform(0.3, 2.0, c).astype(np.float32)
+    x = (rng.standard_normal((n_img, c, m)) * sigma[None, :, None]).astype(np.float16)
+    s0 = sigma * 4.0 / 127.0 * np.where(np.arange(c) % 2 == 0, 0.25, 4.0)
+    theta0 = workloads.theta_for_scale(s0)
+    H.say("distillation training loop: %d steps, %d channels, FP16" % (steps, c))
+
+    xd = H.dev(x.reshape(-1))
+    teacher = xd.clone()
+    y, gy, gx = torch.empty_like(xd), torch.empty_like(xd), torch.empty_like(xd)
+    theta, mm, vv = H.dev(theta0), torch.zeros(c, device="cuda"), torch.zeros(c, device="cuda")
+    gs, gt = torch.empty(c, device="cuda"), torch.empty(c, device="cuda")
+    out = torch.zeros(3, dtype=torch.float64, device="cuda")
+    t = fq.FqTensor.from_torch(n_img, c, m, -127, 127, x=xd, y=y, theta=theta, gy=gy, gx=gx, gs=gs, gtheta=gt)
+    d = fq.FqDistill.from_torch(n_img, c, m, y, teacher, out, gy, lam=lam, upstream=up)
+    ws_b = H.workspace_for(t, fq.FQ_MODE_BACKWARD)
+    ws_d = torch.empty(fq.fq_distill_workspace_bytes(d) // 8, dtype=torch.float64, device="cuda")
+    gpu_loss, gpu_theta = [], []
+    for step in range(1, steps + 1):
+        fq.fq_forward(t)
+        fq.fq_distill_loss(d, ws_d)
+        t.set_adam(fq.FqAdam.from_torch(mm, vv, theta, step=step, **HYPER))
+        fq.fq_backward(t, ws_b)
+        torch.cuda.synchronize()
+        gpu_loss.append(out.cpu().numpy().copy())
+        gpu_theta.append(theta.cpu().numpy().copy())
+
+    th, mo, vo = theta0.copy(), np.zeros(c, np.float32), np.zeros(c, np.float32)
+    ref_loss, ref_theta = [], []
+    eps32, lam32, up32 = float(np.float32(1e-8)), float(np.float32(lam)), float(np.float32(up))
+    for step in range(1, steps + 1):
+        s, active = fq_oracle.scale(th)
+        yo, _ = fq_oracle.forward(x, s, -127, 127, n_img, c, m, want_q=False)
+        mse, cosim, loss, gyo = fq_oracle.distill(yo, x, lam32, eps32, up32)
+        ref_loss.append([mse, cosim, loss])
+        r = fq_oracle.backward(x, gyo, s, th, active, -127, 127, n_img, c, m)
+        th, mo, vo = fq_oracle.adam(r["gtheta"], mo, vo, th, step=step, **HYPER)
+        ref_theta.append(th.copy())
+
+    gpu_loss, ref_loss = np.array(gpu_loss), np.array(ref_loss)
+    assert gpu_loss[-1, 2] < 0.2 * gpu_loss[0, 2], (gpu_loss[0], gpu_loss[-1])
+    # Adam normalises the gradient, so the loss scale `up` does not change the trajectory, and a
+    # last-ulp difference in theta early on stays a last-ulp difference
+    np.testing.assert_allclose(gpu_loss, ref_loss, rtol=1e-4)
+    np.testing.assert_allclose(np.array(gpu_theta), np.array(ref_theta), rtol=1e-4, atol=1e-5)
