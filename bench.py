@@ -47,6 +47,12 @@ WORKLOAD_TEXT = {
 }
 
 
+# HBM bytes per fq_distill_loss call (both kernels) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this command with --copy-calibration, scaled by the plain copy in the same run; see
+# profiles/distill_kernels_feature_and_train_batch.md.  Set an entry to None when its kernels change.
+DISTILL_TRAFFIC_BYTES_PER_CALL = {"feature_fp16_per_channel": 76335808, "train_batch_fp16": 378033465}
+
+
 def distill_bench(args, cases, fq, torch, np):
     """--pass distill: fq_distill_loss (loss and gradient with respect to the student) on one
     student/teacher pair shaped like the workload's tensor.  A step is one call (two kernels).
@@ -97,6 +103,10 @@ def distill_bench(args, cases, fq, torch, np):
     t1 = time.perf_counter()
     ms = ctypes.c_float()
     hip.hipEventElapsedTime(ctypes.byref(ms), ev_a, ev_z)
+    for i in range(args.copy_calibration):           # plain copies of known size for --pmc runs
+        a, _, g = keep[i % ring]
+        g.copy_(a)
+    torch.cuda.synchronize()
     sec_per_step = (t1 - t0) / args.steps
     gpu_sec_per_step = ms.value * 1e-3 / args.steps
     step_bytes = 3 * io_bytes
@@ -104,7 +114,8 @@ def distill_bench(args, cases, fq, torch, np):
     achieved = step_bytes / gpu_sec_per_step / 1e9
     roofline = {"bound": "hbm", "kernel": "fq_distill_loss: distill_stats_kernel + distill_grad_kernel of one call",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": DISTILL_TRAFFIC_BYTES_PER_CALL.get(args.workload),
                 "bytes_per_launch": step_bytes, "avg_us": round(gpu_sec_per_step * 1e6, 2),
                 "method": "one HIP event pair on the launch stream around all timed calls, divided by "
                           "the number of calls"}
