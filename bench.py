@@ -12,9 +12,10 @@ the roofline position of the dominant kernel (the backward kernel, 3b bytes per 
 inside the timed region with HIP events on the launch stream) and the CPU oracle timed on this
 host beside it.
 
-Other workloads (--workload) and the int8 code-emission forward (--pass codes: x in, packed int8
-codes out, b+1 bytes per element) use the same machinery; lists of tensors go through the
-multi-tensor entry points, one launch per pass.
+Other workloads (--workload), the forward alone (--pass forward: 2b bytes per element) and the
+int8 code-emission forward (--pass codes: x in, packed int8 codes out, b+1 bytes per element) use
+the same machinery; lists of tensors go through the multi-tensor entry points, one launch per
+pass.  --pass distill times fq_distill_loss on a student/teacher pair of the workload's shape.
 """
 import argparse
 import ctypes
@@ -34,6 +35,8 @@ EVENT_EVERY = 8                # one bracketed step in this many
 # counter runs summarised in profiles/ (each scaled by a plain copy of known size in the same run).
 # Set to None whenever the backward kernel changes until the counters are taken again.
 TRAFFIC_BYTES_PER_LAUNCH = 44459365
+# The same for the forward kernel (y only) on the headline tensor, from the same counter runs.
+FORWARD_TRAFFIC_BYTES_PER_LAUNCH = 29593203
 
 WORKLOAD_TEXT = {
     "act_fp32_per_tensor": "act_fp32_per_tensor: FP32 1x128x30x40, one scale, codes -128..127",
@@ -161,9 +164,9 @@ def main():
     ap.add_argument("--workload", default="feature_fp16_per_channel",
                     help="one of paper_2511_12653_amd.workloads.WORKLOAD_NAMES (default: the headline "
                          "tensor); lists of tensors go through the multi-tensor entry points")
-    ap.add_argument("--pass", dest="which", default="train", choices=["train", "codes", "distill"],
-                    help="train: forward + STE backward (default); codes: forward that writes only the "
-                         "packed int8 codes; distill: the distillation loss and its gradient for one "
+    ap.add_argument("--pass", dest="which", default="train", choices=["train", "forward", "codes", "distill"],
+                    help="train: forward + STE backward (default); forward: the forward alone (x in, y "
+                         "out); codes: forward that writes only the packed int8 codes; distill: the distillation loss and its gradient for one "
                          "student/teacher pair of the workload's shape (single-tensor workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
@@ -191,16 +194,18 @@ def main():
         sys.exit("bench.py: unknown workload %r (choose from %s)" % (
             args.workload, ", ".join(workloads.WORKLOAD_NAMES)))
     train = args.which == "train"
+    codes = args.which == "codes"
 
     cases = workloads.make(args.workload)
     if args.which == "distill":
         return distill_bench(args, cases, fq, torch, np)
-    if not train:
+    if codes:
         cases = [cs for cs in cases if cs.qmin >= -128 and cs.qmax <= 127]
     multi = len(cases) > 1
     numel = sum(cs.numel for cs in cases)
     io_bytes = sum(cs.numel * cs.itemsize for cs in cases)        # sum over tensors of b * elements
-    set_bytes = 4 * io_bytes if train else io_bytes + numel
+    fwd_bytes = io_bytes + numel if codes else 2 * io_bytes      # bytes one forward launch moves
+    set_bytes = 4 * io_bytes if train else fwd_bytes
     ring = max(2, RING_BYTES // set_bytes) if set_bytes < RING_BYTES else 1
     stream = torch.cuda.current_stream()
     sp = stream.cuda_stream
@@ -221,12 +226,17 @@ def main():
                 keep.append((x, y, gy, gx))
                 group.append(fq.FqTensor.from_torch(cs.outer, cs.channels, cs.inner, cs.qmin, cs.qmax, x=x,
                                                     y=y, gy=gy, gx=gx, gs=gs, gtheta=gtheta, **common))
-            else:
+            elif codes:
                 q = torch.empty(cs.numel, dtype=torch.int8, device="cuda")
                 y = torch.empty_like(x) if (j == 0 and args.copy_calibration) else None
                 keep.append((x, q, y))
                 group.append(fq.FqTensor.from_torch(cs.outer, cs.channels, cs.inner, cs.qmin, cs.qmax, x=x,
                                                     q=q, s=gs, **common))
+            else:
+                y = torch.empty_like(x)
+                keep.append((x, y))
+                group.append(fq.FqTensor.from_torch(cs.outer, cs.channels, cs.inner, cs.qmin, cs.qmax, x=x,
+                                                    y=y, s=gs, **common))
             if j == 0:
                 first_bufs.append((x, y))
         sets.append(fq.fq_tensor_array(group) if multi else group[0])
@@ -325,7 +335,7 @@ def main():
     torch.cuda.synchronize()
 
     sec_per_step = (t1 - t0) / args.steps
-    step_bytes = 5 * io_bytes if train else io_bytes + numel
+    step_bytes = 5 * io_bytes if train else fwd_bytes
     value = step_bytes / sec_per_step / 1e9
 
     roofline = None
@@ -341,17 +351,24 @@ def main():
         if dur[1] and dur[2]:
             t_two, t_one = float(np.mean(dur[2])), float(np.mean(dur[1]))
             t_kernel = t_two - t_one
-            kernel_bytes = 3 * io_bytes if train else io_bytes + numel
+            kernel_bytes = 3 * io_bytes if train else fwd_bytes
             achieved = kernel_bytes / t_kernel / 1e9
             dt = "f16" if cases[0].itemsize == 2 else "f32"
             if train:
                 kname = "backward_multi_kernel<fused>" if multi else "backward_kernel<%s, fused>" % dt
-            else:
+            elif codes:
                 kname = "forward_multi_kernel<codes>" if multi else "forward_kernel<%s, codes>" % dt
-            headline = train and args.workload == "feature_fp16_per_channel"
+            else:
+                kname = "forward_multi_kernel" if multi else "forward_kernel<%s>" % dt
+            headline = args.workload == "feature_fp16_per_channel"
+            traffic = None
+            if headline and train:
+                traffic = TRAFFIC_BYTES_PER_LAUNCH
+            elif headline and not codes:
+                traffic = FORWARD_TRAFFIC_BYTES_PER_LAUNCH
             roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                        "traffic": TRAFFIC_BYTES_PER_LAUNCH if headline else None,
+                        "traffic": traffic,
                         "bytes_per_launch": kernel_bytes, "avg_us": round(t_kernel * 1e6, 2),
                         "method": "HIP events on the launch stream in the timed region: mean(bracket of two "
                                   "launches) - mean(bracket of the first); cancels the event pair's own cost",
@@ -400,7 +417,8 @@ def main():
                 break
             sample.append(cs)
             n_sample += cs.numel
-        sample_bytes = sum((5 * cs.itemsize if train else cs.itemsize + 1) * cs.numel for cs in sample)
+        per_el = lambda cs: 5 * cs.itemsize if train else (cs.itemsize + 1 if codes else 2 * cs.itemsize)
+        sample_bytes = sum(per_el(cs) * cs.numel for cs in sample)
         reps, times = 3, []
         rep = 0
         while rep < reps:
@@ -408,7 +426,7 @@ def main():
             c0 = time.perf_counter()
             for cs in sample:
                 s_, active = fq_oracle.scale(cs.theta, cs.eps, cs.s_min, cs.s_max)
-                fq_oracle.forward(cs.x, s_, cs.qmin, cs.qmax, cs.outer, cs.channels, cs.inner, want_q=not train)
+                fq_oracle.forward(cs.x, s_, cs.qmin, cs.qmax, cs.outer, cs.channels, cs.inner, want_q=codes)
                 if train:
                     fq_oracle.backward(cs.x, cs.gy, s_, cs.theta, active, cs.qmin, cs.qmax,
                                        cs.outer, cs.channels, cs.inner)
@@ -419,17 +437,19 @@ def main():
         cpu = {"value": round(sample_bytes / med / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": "%d of %d tensors of the workload (%d elements, %s), median of %d runs, "
                          "%.2f s each" % (len(sample), len(cases), n_sample,
-                                          "fwd+bwd" if train else "forward with codes", reps, med),
+                                          "fwd+bwd" if train else ("forward with codes" if codes else "forward"), reps, med),
                "elements_per_s": round(n_sample / med, 1)}
 
     out = {
-        "metric": "fake-quant fwd+bwd GB/s" if train else "fake-quant int8 code emission GB/s",
+        "metric": ("fake-quant fwd+bwd GB/s" if train else
+                   "fake-quant int8 code emission GB/s" if codes else "fake-quant forward GB/s"),
         "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.workload] + (", forward + STE backward" if train
-                                                               else ", forward writing int8 codes only"),
+        "config": {"workload": WORKLOAD_TEXT[args.workload] + (", forward + STE backward" if train else
+                                                               ", forward writing int8 codes only" if codes
+                                                               else ", forward only"),
                    "tensors": len(cases), "launches_per_step": per_step, "elements": numel,
                    "bytes_per_step": step_bytes, "ring_buffer_sets": int(ring),
                    "ring_bytes": int(ring * set_bytes)},
