@@ -93,3 +93,41 @@ def test_nan_poisons_its_position_only(oracle):
     assert np.array_equal(np.isnan(ga), np.isnan(r[3]))
     assert np.isnan(ga[0, :, 4]).all() and not np.isnan(np.delete(ga, 4, axis=2)).any()
     np.testing.assert_allclose(np.delete(ga, 4, axis=2), np.delete(r[3], 4, axis=2), rtol=1e-6)
+
+
+def test_clamped_norms(oracle):
+    """Norms below eps on either side.  Values and, away from a clamped student norm, gradients are
+    pinned to the library routines; a zero teacher vector keeps the division finite.  Where the
+    student's own norm is clamped the gradient is the derivative of the function as defined
+    (max(||a||, eps) is locally the constant eps), pinned by central differences of the oracle's
+    own loss, which are exact there up to rounding: with the norm clamped cos is linear in a and
+    the MSE is quadratic.  (Autograd of the library's cosine differs at such positions: it uses
+    the clamped value of the norm but still differentiates the unclamped norm.)"""
+    rng = np.random.default_rng(12)
+    a = rng.standard_normal((2, 5, 8)).astype(np.float32)
+    b = rng.standard_normal((2, 5, 8)).astype(np.float32)
+    unit = np.float32(2.0 ** -30)
+    a[0, :, 1] = rng.integers(-16, 17, 5).astype(np.float32) * unit     # ||a|| ~ 2e-8 < eps
+    a[1, :, 3] = rng.integers(-16, 17, 5).astype(np.float32) * unit
+    b[0, :, 5] = 0.0
+    b[1, :, 3] *= np.float32(1e-7)                                       # both below eps at (1, 3)
+    eps, lam = 1e-6, 0.8
+    mse, cosim, loss, ga = oracle.distill(a, b, lam=lam, eps=eps)
+    r_mse, r_cos, r_loss, r_g = _torch_ref(a, b, lam, eps, 1.0)
+    assert np.isfinite(ga).all()
+    assert abs(mse - r_mse) <= 1e-12 * r_mse and abs(cosim - r_cos) <= 1e-12 and abs(loss - r_loss) <= 1e-12 * r_loss
+    clamped = np.zeros(a.shape, bool)
+    clamped[0, :, 1] = clamped[1, :, 3] = True
+    na = np.sqrt((a.astype(np.float64) ** 2).sum(axis=1))
+    assert na[0, 1] < eps and na[1, 3] < eps and (np.delete(na.reshape(-1), [1, 11]) > 0.1).all()
+    np.testing.assert_allclose(ga[~clamped].astype(np.float64), r_g[~clamped], rtol=2e-6, atol=1e-12)
+    h = np.float32(2.0 ** -34)                    # a +- h is exact for the multiples of 2^-30 above
+    for n_, m_ in ((0, 1), (1, 3)):
+        for c_ in range(5):
+            ap, am = a.copy(), a.copy()
+            ap[n_, c_, m_] += h
+            am[n_, c_, m_] -= h
+            fd = (oracle.distill(ap, b, lam, eps, want_grad=False)[2] -
+                  oracle.distill(am, b, lam, eps, want_grad=False)[2]) / (2.0 * float(h))
+            assert abs(float(ga[n_, c_, m_]) - fd) <= 2e-6 * abs(fd) + 1e-9, (n_, c_, m_, ga[n_, c_, m_], fd)
+    assert np.abs(ga[0, :, 1]).max() > 1e3        # the regime where the clamp matters: cos is far from 0
