@@ -144,9 +144,11 @@ def test_zero_norm_positions_and_identical_maps(oracle):
     b[1, :, 100:140] = 0.0      # teacher norm below eps: cos = 0 there
     a[1, :, 200] = 0.0
     b[1, :, 200] = 0.0
+    a[0, :, 20:24] *= np.float32(1e-9)   # tiny but non-zero student: clamped norm, cos far from zero
     _run(a, b, 0.7, oracle, label="zero-norm")
     # student == teacher: every term of the gradient cancels; what is left is noise around
     # 1e-16 of the cancelling terms (themselves below 1e-3 here)
+    a, _ = _pair(15, (2, 16, 256), np.float32)
     got, ga = _run(a, a.copy(), 0.7, oracle, label="identical", noise_floor=1e-18)
     assert got[0] == 0.0 and np.abs(ga).max() <= 1e-18
 
