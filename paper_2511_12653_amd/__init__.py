@@ -3,6 +3,7 @@
 `workloads` generates seeded synthetic inputs (numpy only).  The GPU entry points live in
 `binding` (thin ctypes marshalling onto the C-ABI library built from csrc/); it is imported
 on first use and raises if the compiled library is missing -- there is no CPU fallback.
+`fake_quantize` (module `autograd`) wraps the forward and backward calls in a torch.autograd Function.
 """
 from . import workloads  # noqa: F401
 
@@ -13,6 +14,9 @@ _API = ("fq_forward", "fq_backward", "fq_multi_tensor", "fq_workspace_bytes", "f
 
 
 def __getattr__(name):
+    if name == "fake_quantize":
+        from .autograd import fake_quantize
+        return fake_quantize
     if name == "binding" or name in _API:
         import importlib
         mod = importlib.import_module(__name__ + ".binding")
