@@ -41,6 +41,7 @@ bool overlap(const void *a, size_t abytes, const void *b, size_t bbytes)
 struct Plan {
     long long numel = 0;
     unsigned slabs = 0, cps = 0, chunk = 0;
+    unsigned sub = 0;            // first-level ticket slots per channel (0: one slot per channel)
     long long blocks = 0;
 };
 
@@ -87,6 +88,7 @@ fq_status plan_tensor(const fq_tensor &t, Plan &p)
     p.cps = (unsigned)best_cps;
     p.chunk = (unsigned)best_chunk;
     p.blocks = slabs * best_cps;
+    p.sub = t.outer * best_cps > (long long)kTicketFanIn ? kTicketSubSlots : 0u;   // blocks per channel
     return FQ_OK;
 }
 
@@ -136,6 +138,7 @@ struct Layout {
     std::vector<Plan> plans;
     long long blocks = 0;        // grid of the main kernel
     long long channels = 0;      // grid of the finalize kernel
+    long long slots = 0;         // 64-bit ticket / exchange slots (backward)
     long long partials = 0;      // doubles
     size_t table_bytes = 0, partial_off = 0, counter_off = 0, total = 0;
     bool any_empty_with_channels = false;
@@ -152,8 +155,9 @@ fq_status make_layout(const fq_tensor *ts, int n, int mode, Layout &L)
         if (st != FQ_OK) return st;
         L.blocks += L.plans[(size_t)i].blocks;
         L.channels += ts[i].channels;
+        L.slots += ts[i].channels * (1 + (long long)L.plans[(size_t)i].sub);
         if (L.plans[(size_t)i].numel == 0 && ts[i].channels > 0) L.any_empty_with_channels = true;
-        if (L.blocks > kMaxBlocks || L.channels > kMaxBlocks) return FQ_ERR_SHAPE;
+        if (L.blocks > kMaxBlocks || L.channels > kMaxBlocks || L.slots > 64 * kMaxBlocks) return FQ_ERR_SHAPE;
     }
     L.partials = L.blocks;
     L.table_bytes = round_up((size_t)n * sizeof(DevTensor), kAlign);
@@ -162,7 +166,7 @@ fq_status make_layout(const fq_tensor *ts, int n, int mode, Layout &L)
     L.total = L.table_bytes;
     if (mode == FQ_MODE_BACKWARD) {
         L.counter_off = L.partial_off + round_up((size_t)L.partials * sizeof(double), kAlign);
-        L.total = L.counter_off + round_up((size_t)L.channels * sizeof(unsigned long long), kAlign);
+        L.total = L.counter_off + round_up((size_t)L.slots * sizeof(unsigned long long), kAlign);
     }
     if (L.total < kAlign) L.total = kAlign;
     return FQ_OK;
@@ -173,7 +177,7 @@ void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *wo
                  std::vector<DevTensor> &out)
 {
     out.resize((size_t)n);
-    long long block = 0, chan = 0;
+    long long block = 0, chan = 0, slot = 0;
     for (int i = 0; i < n; ++i) {
         const fq_tensor &t = ts[i];
         const Plan &p = L.plans[(size_t)i];
@@ -182,7 +186,7 @@ void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *wo
         d.x = t.x; d.y = t.y; d.q = t.q; d.theta = t.theta; d.s = t.s;
         d.gy = t.gy; d.gx = t.gx; d.gs = t.gs; d.gtheta = t.gtheta;
         d.partial = workspace ? (double *)(workspace + L.partial_off) + block : nullptr;
-        d.slot = workspace ? (unsigned long long *)(workspace + L.counter_off) + chan : nullptr;
+        d.slot = workspace ? (unsigned long long *)(workspace + L.counter_off) + slot : nullptr;
         d.inner = t.inner;
         d.slabs = p.slabs;
         d.channels = (unsigned)t.channels;
@@ -191,6 +195,7 @@ void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *wo
         d.chunk = p.chunk;
         d.block_begin = (unsigned)block;
         d.chan_begin = (unsigned)chan;
+        d.sub = p.sub;
         d.dtype = t.dtype;
         d.lo = (float)t.qmin;
         d.hi = (float)t.qmax;
@@ -208,6 +213,7 @@ void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *wo
         }
         block += p.blocks;
         chan += t.channels;
+        slot += t.channels * (1 + (long long)p.sub);
     }
 }
 

@@ -10,6 +10,8 @@ constexpr int kBlock = 256;          // threads per block: four 64-wide wavefron
 constexpr int kVecBytes = 16;        // one 128-bit global load/store per lane
 constexpr int kChunkVecs = 1280;     // at most this many 128-bit vectors per block (20 KiB)
 constexpr int kComputeUnits = 256;   // MI355X; used by the host to balance blocks over the chip
+constexpr unsigned kTicketFanIn = 64;   // more blocks than this per channel: tickets are drawn in two levels
+constexpr unsigned kTicketSubSlots = 32;
 
 // Device-side view of one tensor.  Built on the host; passed as a kernel argument for
 // single-tensor calls, or as an array in device memory for the multi-tensor launch.
@@ -24,7 +26,8 @@ struct DevTensor {
     float *gs;
     float *gtheta;
     double *partial;           // [slabs * cps] per-block partial sums of gy*t (backward)
-    unsigned long long *slot;  // [channels] exchange slot / arrival tickets, zero between calls (backward)
+    unsigned long long *slot;  // [channels] exchange slot / arrival tickets, then [channels][sub] first-level
+                               // tickets; all zero between calls (backward)
     long long inner;           // elements per slab
     unsigned slabs;            // outer * channels
     unsigned channels;
@@ -33,6 +36,7 @@ struct DevTensor {
     unsigned chunk;            // elements per chunk, a multiple of the vector width
     unsigned block_begin;      // first block of this tensor in the grid
     unsigned chan_begin;       // first channel of this tensor in the finalize grid
+    unsigned sub;              // first-level ticket slots per channel (0: the channel's blocks share one slot)
     int dtype;                 // 0 = FP16, 1 = FP32
     float lo, hi;              // (float)qmin, (float)qmax
     float eps, s_min, s_max;

@@ -527,7 +527,8 @@ __device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c,
 //                         one atomic round trip, the payload travels in the atomic itself;
 //   more                  each block stores its sum, waits for that store, then draws a ticket
 //                         from the slot; the block with the last ticket re-reads all sums in index
-//                         order and clears the slot.
+//                         order and clears the slot.  Beyond kTicketFanIn blocks per channel the
+//                         tickets are drawn in two levels (kTicketSubSlots first-level slots).
 // The slot is zero between calls.  (A sum of +0.0 is swapped in as -0.0 so that it differs from
 // an empty slot; it adds the same.)
 // Without FUSED the sums are only stored and finalize_kernel adds them in a second launch.
@@ -573,10 +574,30 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
             // would flush the whole L2 once per block).
             __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            const unsigned long long ticket = __hip_atomic_fetch_add(&d.slot[ck.channel], 1ull, __ATOMIC_RELAXED,
+            unsigned long long *top = &d.slot[ck.channel];
+            unsigned long long expected = bpc;
+            bool draw_top = true;
+            if (d.sub) {
+                // Hundreds of blocks drawing from one address queue up behind each other at the
+                // memory-side atomic unit.  Block j of the channel draws from sub-slot j mod sub
+                // first; only the last arrival there goes on to the channel's own slot.
+                const unsigned o = ck.slab / d.channels;
+                const unsigned j = o * d.cps + (local_block - ck.slab * d.cps);
+                const unsigned k = j % d.sub;
+                const unsigned long long arrivals = (bpc - k + d.sub - 1u) / d.sub;
+                unsigned long long *first = d.slot + d.channels + (size_t)ck.channel * d.sub + k;
+                const unsigned long long t1 = __hip_atomic_fetch_add(first, 1ull, __ATOMIC_RELAXED,
                                                                      __HIP_MEMORY_SCOPE_AGENT);
-            last = (ticket == (unsigned long long)(bpc - 1u)) ? 1u : 0u;
-            if (last) __hip_atomic_store(&d.slot[ck.channel], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                draw_top = t1 == arrivals - 1ull;
+                if (draw_top) __hip_atomic_store(first, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                expected = d.sub;                      // bpc > sub, so every sub-slot is in use
+            }
+            if (draw_top) {
+                const unsigned long long ticket = __hip_atomic_fetch_add(top, 1ull, __ATOMIC_RELAXED,
+                                                                         __HIP_MEMORY_SCOPE_AGENT);
+                last = (ticket == expected - 1ull) ? 1u : 0u;
+                if (last) __hip_atomic_store(top, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         is_last = last;
     }

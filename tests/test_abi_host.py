@@ -110,6 +110,13 @@ def test_workspace_bytes(fq):
     assert fwd % 256 == 0 and bwd % 256 == 0 and fwd >= 256
     assert bwd >= fwd + 3840 * 8 + 128 * 8
     assert bwd <= fwd + 3840 * 8 + 128 * 8 + 3 * 256
+    # one scale for 7 372 800 FP16 elements = 921 600 vectors: 720 blocks of 1280 vectors share the
+    # channel, more than 64, so it gets 32 first-level ticket slots beside its own: 33 slots
+    pt = _desc(fq, outer=1, channels=1, inner=7372800, x=1 << 32, y=2 << 32, gy=3 << 32, gx=4 << 32)
+    assert fq.fq_workspace_bytes(pt, 2) == fq.fq_workspace_bytes(pt, 1) + (720 * 8 + 128) + 512
+    # 64 blocks per channel still share one slot
+    few = _desc(fq, outer=32, channels=3, inner=19200, x=1 << 32, y=2 << 32, gy=3 << 32, gx=4 << 32)
+    assert fq.fq_workspace_bytes(few, 2) == fq.fq_workspace_bytes(few, 1) + 32 * 3 * 2 * 8 + 256
     two = fq.fq_workspace_bytes([t, t], 2)
     assert two >= 2 * (3840 * 8 + 128 * 8)
     assert fq.fq_workspace_bytes([], 2) == 256
