@@ -63,7 +63,6 @@ template <typename T> struct Pack<T, 1> {
 };
 
 typedef double double2v __attribute__((ext_vector_type(2)));
-typedef double double4v __attribute__((ext_vector_type(4)));
 
 // Which tile / channel group a wavefront works on, and where its lane's V positions start.
 struct Where {
