@@ -54,16 +54,16 @@ def test_one_channel_many_blocks():
     _repeat(case, "stress/one_channel", 200)
 
 
-@pytest.mark.parametrize("outer, channels, inner", [
-    (1, 1, 64 * 5120),          # 64 blocks: the last count that shares one slot
-    (1, 1, 65 * 5120),          # 65 blocks: two-level tickets, first-level slots see 3 or 2 arrivals
-    (1, 1, 97 * 5120 + 13),     # ragged last block
-    (33, 3, 2 * 5120),          # 66 blocks per channel spread over 33 slabs, three channels
+@pytest.mark.parametrize("dtype, outer, channels, inner", [
+    (np.float16, 32, 3, 19200),     # 2 blocks per slab: 64 per channel, the last count that shares one slot
+    (np.float16, 33, 3, 19200),     # 66 per channel: two-level tickets, first-level slots see 3 or 2 arrivals
+    (np.float32, 1, 1, 65 * 5120),  # one scale, well over a hundred blocks
+    (np.float32, 1, 1, 97 * 5120 + 13),   # ragged last block
 ])
-def test_ticket_levels_around_the_threshold(outer, channels, inner):
+def test_ticket_levels_around_the_threshold(dtype, outer, channels, inner):
     rng = np.random.Generator(np.random.Philox(outer * 1000 + channels))
-    x = (rng.standard_normal((outer, channels, inner)) * 2).astype(np.float32)
-    gy = rng.standard_normal(x.shape).astype(np.float32)
+    x = (rng.standard_normal((outer, channels, inner)) * 2).astype(dtype)
+    gy = rng.standard_normal(x.shape).astype(dtype)
     theta = workloads.theta_for_scale(rng.uniform(0.02, 0.05, channels))
     case = workloads.TensorCase("lv", x.shape, outer, channels, inner, -128, 127, x, theta, gy)
     _repeat(case, "stress/levels %dx%dx%d" % (outer, channels, inner), 20)
