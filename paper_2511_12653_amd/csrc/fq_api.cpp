@@ -41,7 +41,7 @@ bool overlap(const void *a, size_t abytes, const void *b, size_t bbytes)
 struct Plan {
     long long numel = 0;
     unsigned slabs = 0, cps = 0, chunk = 0;
-    unsigned sub = 0;            // first-level ticket slots per channel (0: one slot per channel)
+    unsigned sub = 0;            // extra slots per channel: pair slots (2) or first-level ticket slots (32)
     long long blocks = 0;
 };
 
@@ -88,7 +88,9 @@ fq_status plan_tensor(const fq_tensor &t, Plan &p)
     p.cps = (unsigned)best_cps;
     p.chunk = (unsigned)best_chunk;
     p.blocks = slabs * best_cps;
-    p.sub = t.outer * best_cps > (long long)kTicketFanIn ? kTicketSubSlots : 0u;   // blocks per channel
+    const long long per_channel = t.outer * best_cps;                             // blocks per channel
+    p.sub = per_channel > (long long)kTicketFanIn ? kTicketSubSlots
+            : (per_channel > 2 && per_channel <= (long long)kTreeBlocks) ? 2u : 0u;
     return FQ_OK;
 }
 

@@ -12,6 +12,7 @@ constexpr int kChunkVecs = 1280;     // at most this many 128-bit vectors per bl
 constexpr int kComputeUnits = 256;   // MI355X; used by the host to balance blocks over the chip
 constexpr unsigned kTicketFanIn = 64;   // more blocks than this per channel: tickets are drawn in two levels
 constexpr unsigned kTicketSubSlots = 32;
+constexpr unsigned kTreeBlocks = 4;      // up to this many blocks per channel combine by atomic exchange alone
 
 // Device-side view of one tensor.  Built on the host; passed as a kernel argument for
 // single-tensor calls, or as an array in device memory for the multi-tensor launch.
@@ -36,7 +37,8 @@ struct DevTensor {
     unsigned chunk;            // elements per chunk, a multiple of the vector width
     unsigned block_begin;      // first block of this tensor in the grid
     unsigned chan_begin;       // first channel of this tensor in the finalize grid
-    unsigned sub;              // first-level ticket slots per channel (0: the channel's blocks share one slot)
+    unsigned sub;              // extra slots per channel after the [channels] main ones: 0, 2 (pair slots of
+                               // the exchange tree, 3 or 4 blocks per channel) or kTicketSubSlots
     int dtype;                 // 0 = FP16, 1 = FP32
     float lo, hi;              // (float)qmin, (float)qmax
     float eps, s_min, s_max;

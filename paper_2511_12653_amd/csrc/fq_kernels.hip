@@ -525,6 +525,7 @@ __device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c,
 //   2 blocks per channel  each swaps its sum into the channel's 64-bit slot; the one that finds
 //                         its partner's sum there adds the two (a+b = b+a) and clears the slot:
 //                         one atomic round trip, the payload travels in the atomic itself;
+//   3 or 4                two rounds of that exchange, pairs first (two more slots per channel);
 //   more                  each block stores its sum, waits for that store, then draws a ticket
 //                         from the slot; the block with the last ticket re-reads all sums in index
 //                         order and clears the slot.  Beyond kTicketFanIn blocks per channel the
@@ -567,6 +568,38 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
                 const double both = (__builtin_bit_cast(double, theirs) + total) + 0.0;
                 write_channel_grads(d, ck.channel, both, bs);
             }
+        } else if (bpc <= kTreeBlocks) {
+            // Three or four blocks: two rounds of the same exchange, associated as finalize_channel
+            // associates its sums, (p0 + p1) + (p2 + p3) with an absent p3 counting as +0.0, so the
+            // bits equal those of the two-launch mode.  Unlike the tickets below this needs no wait
+            // for the block's own gx stores and no re-read of the partial sums.
+            const unsigned o = ck.slab / d.channels;
+            const unsigned j = o * d.cps + (local_block - ck.slab * d.cps);
+            double pair_sum = total + 0.0;                 // block 2 of 3 has no partner
+            bool carry_on = true;
+            if (!(bpc == 3u && j == 2u)) {
+                unsigned long long *pair = d.slot + d.channels + (size_t)ck.channel * 2u + (j >> 1);
+                unsigned long long mine = __builtin_bit_cast(unsigned long long, total);
+                if (mine == 0ull) mine = 0x8000000000000000ull;
+                const unsigned long long theirs = __hip_atomic_exchange(pair, mine, __ATOMIC_RELAXED,
+                                                                        __HIP_MEMORY_SCOPE_AGENT);
+                carry_on = theirs != 0ull;
+                if (carry_on) {
+                    __hip_atomic_store(pair, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    pair_sum = __builtin_bit_cast(double, theirs) + total;
+                }
+            }
+            if (carry_on) {
+                unsigned long long mine = __builtin_bit_cast(unsigned long long, pair_sum);
+                if (mine == 0ull) mine = 0x8000000000000000ull;
+                const unsigned long long theirs = __hip_atomic_exchange(&d.slot[ck.channel], mine, __ATOMIC_RELAXED,
+                                                                        __HIP_MEMORY_SCOPE_AGENT);
+                if (theirs != 0ull) {
+                    __hip_atomic_store(&d.slot[ck.channel], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const double all = (__builtin_bit_cast(double, theirs) + pair_sum) + 0.0;
+                    write_channel_grads(d, ck.channel, all, bs);
+                }
+            }
         } else {
             // Agent-scope store: written through to where every XCD can see it.  Wait until it
             // has completed, then take a ticket.  Only the partial has to be published, so no
@@ -601,7 +634,7 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
         }
         is_last = last;
     }
-    if (FUSED && bpc > 2u) {
+    if (FUSED && bpc > kTreeBlocks) {
         __syncthreads();
         if (is_last) {
             // every other block of this channel completed its partial store before its ticket

@@ -67,3 +67,34 @@ def test_ticket_levels_around_the_threshold(dtype, outer, channels, inner):
     theta = workloads.theta_for_scale(rng.uniform(0.02, 0.05, channels))
     case = workloads.TensorCase("lv", x.shape, outer, channels, inner, -128, 127, x, theta, gy)
     _repeat(case, "stress/levels %dx%dx%d" % (outer, channels, inner), 20)
+
+
+@pytest.mark.parametrize("blocks_per_channel", [1, 2, 3, 4, 5, 8, 64, 66, 130])
+def test_every_combination_protocol_equals_the_two_launch_mode_bitwise(blocks_per_channel):
+    """One block per slab (8192 FP16 elements), so a channel has exactly `outer` blocks: direct
+    write, exchange, exchange tree, tickets, two-level tickets.  Each must give the bits of the
+    two-launch mode (and the oracle's values); channel 0 has an all-zero upstream gradient."""
+    outer, channels, inner = blocks_per_channel, 5, 8192
+    rng = np.random.Generator(np.random.Philox(7000 + outer))
+    x = (rng.standard_normal((outer, channels, inner)) * 2).astype(np.float16)
+    gy = rng.standard_normal(x.shape).astype(np.float16)
+    gy[:, 0, :] = 0.0
+    theta = workloads.theta_for_scale(rng.uniform(0.02, 0.05, channels))
+    case = workloads.TensorCase("proto", x.shape, outer, channels, inner, -128, 127, x, theta, gy)
+    H.say("stress/protocols: %d blocks per channel" % outer)
+    got = {}
+    for flags in (0, fq.FQ_FLAG_TWO_PASS):
+        dc = H.DeviceCase(case, want_q=False, flags=flags)
+        ws = H.workspace_for(dc.desc, fq.FQ_MODE_BACKWARD)
+        for rep in range(3):                       # the slots must be back at zero after every call
+            dc.gs.fill_(float("nan"))
+            dc.gtheta.fill_(float("nan"))
+            fq.fq_backward(dc.desc, ws)
+        torch.cuda.synchronize()
+        if flags == 0:
+            ref = H.oracle_forward(case)
+            H.check_backward(dc, ref[0], ref[1], "stress/protocols")
+        got[flags] = (dc.host("gs"), dc.host("gtheta"))
+    for a, b in zip(got[0], got[fq.FQ_FLAG_TWO_PASS]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (blocks_per_channel, a, b)
+    assert got[0][0][0] == 0.0 and not np.signbit(got[0][0][0])
