@@ -34,9 +34,9 @@ EVENT_EVERY = 8                # one bracketed step in this many
 # HBM bytes per backward launch on the headline tensor, from the rocprofv3 FETCH_SIZE / WRITE_SIZE
 # counter runs summarised in profiles/ (each scaled by a plain copy of known size in the same run).
 # Set to None whenever the backward kernel changes until the counters are taken again.
-TRAFFIC_BYTES_PER_LAUNCH = 44472331
+TRAFFIC_BYTES_PER_LAUNCH = 44454849
 # The same for the forward kernel (y only) on the headline tensor, from the same counter runs.
-FORWARD_TRAFFIC_BYTES_PER_LAUNCH = 29593231
+FORWARD_TRAFFIC_BYTES_PER_LAUNCH = 29578918
 
 WORKLOAD_TEXT = {
     "act_fp32_per_tensor": "act_fp32_per_tensor: FP32 1x128x30x40, one scale, codes -128..127",

@@ -118,6 +118,22 @@ size_t fq_workspace_bytes(const fq_tensor *ts, int n, int mode);
 fq_status fq_validate(const fq_tensor *ts, int n, int mode);
 
 /*
+ * How the library cuts one tensor up (pure host function, touches no GPU; for tests and tuning).
+ * A unit is what one partial sum of the backward covers: a block's chunk, or, for tensors whose
+ * slabs are short, a whole slab handled by one wavefront (only in launches with thousands of blocks;
+ * this call describes the tensor launched on its own).
+ */
+typedef struct fq_layout_info {
+    int64_t blocks;              /* grid blocks of the forward / backward kernel */
+    int64_t units_per_channel;   /* partial sums combined per channel: 1 direct, 2 exchange, 3-4 exchange
+                                    tree, more: tickets (two-level when extra_slots >= 16) */
+    int64_t unit_elems;          /* elements per unit (the last unit of a slab may be shorter) */
+    int32_t wave_units;          /* 1: one wavefront per slab, four slabs to a block */
+    int32_t extra_slots;         /* 64-bit workspace slots per channel beside the channel's own */
+} fq_layout_info;
+fq_status fq_layout(const fq_tensor *t, fq_layout_info *info);
+
+/*
  * Zero a workspace on `stream` (a fill kernel, not a memset, so it may be captured in a
  * HIP graph).  A workspace must be zeroed once before its first use by fq_backward /
  * fq_multi_tensor in backward mode (memory that is already all zero, e.g. torch.zeros,

@@ -9,7 +9,7 @@ from . import workloads  # noqa: F401
 
 _API = ("fq_forward", "fq_backward", "fq_multi_tensor", "fq_workspace_bytes", "fq_workspace_init",
         "fq_validate", "fq_status_string", "fq_plan_create", "fq_plan_run", "fq_plan_run_adam", "fq_plan_destroy",
-        "fq_distill_loss", "fq_distill_workspace_bytes", "FqDistill", "FqTensor", "FqAdam", "FqTensorArray", "fq_tensor_array", "FqError", "library_path",
+        "fq_layout", "FqLayoutInfo", "fq_distill_loss", "fq_distill_workspace_bytes", "FqDistill", "FqTensor", "FqAdam", "FqTensorArray", "fq_tensor_array", "FqError", "library_path",
         "FQ_F16", "FQ_F32", "FQ_FLAG_NO_DX", "FQ_FLAG_TWO_PASS", "FQ_MODE_FORWARD", "FQ_MODE_BACKWARD")
 
 

@@ -132,6 +132,12 @@ class FqDistill(ctypes.Structure):
         return self
 
 
+class FqLayoutInfo(ctypes.Structure):
+    """Mirror of `struct fq_layout_info`."""
+    _fields_ = [("blocks", ctypes.c_int64), ("units_per_channel", ctypes.c_int64),
+                ("unit_elems", ctypes.c_int64), ("wave_units", ctypes.c_int32), ("extra_slots", ctypes.c_int32)]
+
+
 class FqError(RuntimeError):
     def __init__(self, status):
         self.status = int(status)
@@ -165,6 +171,8 @@ _lib.fq_distill_workspace_bytes.argtypes = [ctypes.POINTER(FqDistill)]
 _lib.fq_distill_workspace_bytes.restype = ctypes.c_size_t
 _lib.fq_distill_loss.argtypes = [ctypes.POINTER(FqDistill), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fq_distill_loss.restype = ctypes.c_int
+_lib.fq_layout.argtypes = [ctypes.POINTER(FqTensor), ctypes.POINTER(FqLayoutInfo)]
+_lib.fq_layout.restype = ctypes.c_int
 _lib.fq_status_string.argtypes = [ctypes.c_int]
 _lib.fq_status_string.restype = ctypes.c_char_p
 
@@ -274,3 +282,9 @@ def fq_distill_workspace_bytes(d: FqDistill) -> int:
 def fq_distill_loss(d: FqDistill, workspace, stream=None):
     p, nbytes = _ws(workspace)
     _check(_lib.fq_distill_loss(ctypes.byref(d), p, nbytes, _stream(stream)))
+
+
+def fq_layout(t: FqTensor) -> FqLayoutInfo:
+    info = FqLayoutInfo()
+    _check(_lib.fq_layout(ctypes.byref(t), ctypes.byref(info)))
+    return info

@@ -17,6 +17,7 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr long long kMaxBlocks = 0x7fffffffLL;
+constexpr long long kWaveUnitsMinBlocks = 4096;   // 16 blocks per compute unit
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -42,8 +43,22 @@ struct Plan {
     long long numel = 0;
     unsigned slabs = 0, cps = 0, chunk = 0;
     unsigned sub = 0;            // extra slots per channel: pair slots (2) or first-level ticket slots (32)
-    long long blocks = 0;
+    bool short_slabs = false;    // a slab fits one wavefront's chunk
+    bool waves = false;          // short slabs in a launch with blocks to spare: one wavefront per slab,
+                                 // four slabs to a block
+    long long blocks = 0;        // grid blocks
+    long long units = 0;         // partial sums: one per block, or one per slab with `waves'
 };
+
+// Slots a channel needs beside its own, by the number of units (blocks or wavefronts) that
+// combine their sums for it: pair slots of the exchange tree, or first-level ticket slots.
+unsigned extra_slots(long long units_per_channel)
+{
+    if (units_per_channel > (long long)kTicketManyUnits) return kTicketManySubSlots;
+    if (units_per_channel > (long long)kTicketFanIn) return kTicketSubSlots;
+    if (units_per_channel > 2 && units_per_channel <= (long long)kTreeBlocks) return 2u;
+    return 0u;
+}
 
 // Split every [outer, channel] slab into cps equal chunks of at most kChunkVecs vectors each,
 // chunk length a multiple of the vector width so all chunks of a slab share one alignment.
@@ -51,7 +66,7 @@ struct Plan {
 // one with the smallest estimated makespan: (blocks per compute unit, rounded up) x (rows per
 // wavefront + 1 for the per-block prologue).  Large tensors end up with the biggest chunks, a
 // tensor whose block count is a small multiple of the CU count avoids a mostly-empty last round.
-fq_status plan_tensor(const fq_tensor &t, Plan &p)
+fq_status plan_tensor(const fq_tensor &t, Plan &p, bool allow_waves)
 {
     if (t.dtype != FQ_F16 && t.dtype != FQ_F32) return FQ_ERR_DTYPE;
     if (t.outer < 0 || t.channels < 0 || t.inner < 0) return FQ_ERR_SHAPE;
@@ -67,6 +82,21 @@ fq_status plan_tensor(const fq_tensor &t, Plan &p)
     }
     const long long vec = kVecBytes / (t.dtype == FQ_F16 ? 2 : 4);
     const long long slab_vecs = (t.inner + vec - 1) / vec;
+    // Slabs that one wavefront covers (320 vectors; one vector more than the aligned part can hold
+    // is left for a misaligned head) go one to a wavefront: a block per slab would leave most of
+    // its lanes idle and pay a block's prologue and reduction for a few KB.  Only where the launch
+    // has blocks to spare (allow_waves): a small tensor on its own is bound by latency and is
+    // better off spread over four times as many blocks.
+    p.short_slabs = slab_vecs + 1 <= kWaveChunkVecs;
+    if (allow_waves && p.short_slabs) {
+        p.waves = true;
+        p.cps = 1;
+        p.chunk = (unsigned)((t.inner + vec - 1) / vec * vec);
+        p.units = slabs;
+        p.blocks = (slabs + kBlock / 64 - 1) / (kBlock / 64);
+        p.sub = extra_slots(t.outer);
+        return FQ_OK;
+    }
     const int max_rows = kChunkVecs / kBlock;
     long long best_cps = 0, best_chunk = 0;
     double best_cost = 0.0;
@@ -88,15 +118,15 @@ fq_status plan_tensor(const fq_tensor &t, Plan &p)
     p.cps = (unsigned)best_cps;
     p.chunk = (unsigned)best_chunk;
     p.blocks = slabs * best_cps;
+    p.units = p.blocks;
     const long long per_channel = t.outer * best_cps;                             // blocks per channel
-    p.sub = per_channel > (long long)kTicketFanIn ? kTicketSubSlots
-            : (per_channel > 2 && per_channel <= (long long)kTreeBlocks) ? 2u : 0u;
+    p.sub = extra_slots(per_channel);
     return FQ_OK;
 }
 
 fq_status validate_one(const fq_tensor &t, int mode, Plan &p)
 {
-    fq_status st = plan_tensor(t, p);
+    fq_status st = plan_tensor(t, p, false);
     if (st != FQ_OK) return st;
     if (!(t.qmin <= 0 && 0 <= t.qmax && t.qmin < t.qmax) || t.qmin < -32768 || t.qmax > 32768)
         return FQ_ERR_QRANGE;
@@ -156,12 +186,27 @@ fq_status make_layout(const fq_tensor *ts, int n, int mode, Layout &L)
         fq_status st = validate_one(ts[i], mode, L.plans[(size_t)i]);
         if (st != FQ_OK) return st;
         L.blocks += L.plans[(size_t)i].blocks;
+        L.partials += L.plans[(size_t)i].units;
         L.channels += ts[i].channels;
         L.slots += ts[i].channels * (1 + (long long)L.plans[(size_t)i].sub);
         if (L.plans[(size_t)i].numel == 0 && ts[i].channels > 0) L.any_empty_with_channels = true;
         if (L.blocks > kMaxBlocks || L.channels > kMaxBlocks || L.slots > 64 * kMaxBlocks) return FQ_ERR_SHAPE;
     }
-    L.partials = L.blocks;
+    if (L.blocks >= kWaveUnitsMinBlocks) {
+        // enough blocks to fill the chip many times over: short-slab tensors switch to one
+        // wavefront per slab (fewer blocks, partial sums and slots; the limits above still hold)
+        for (int i = 0; i < n; ++i) {
+            Plan &p = L.plans[(size_t)i];
+            if (!p.short_slabs || p.numel == 0) continue;
+            L.blocks -= p.blocks;
+            L.partials -= p.units;
+            L.slots -= ts[i].channels * (1 + (long long)p.sub);
+            (void)plan_tensor(ts[i], p, true);
+            L.blocks += p.blocks;
+            L.partials += p.units;
+            L.slots += ts[i].channels * (1 + (long long)p.sub);
+        }
+    }
     L.table_bytes = round_up((size_t)n * sizeof(DevTensor), kAlign);
     L.partial_off = L.table_bytes;
     L.counter_off = L.partial_off;
@@ -179,7 +224,7 @@ void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *wo
                  std::vector<DevTensor> &out)
 {
     out.resize((size_t)n);
-    long long block = 0, chan = 0, slot = 0;
+    long long block = 0, chan = 0, slot = 0, unit = 0;
     for (int i = 0; i < n; ++i) {
         const fq_tensor &t = ts[i];
         const Plan &p = L.plans[(size_t)i];
@@ -187,7 +232,7 @@ void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *wo
         std::memset(&d, 0, sizeof d);
         d.x = t.x; d.y = t.y; d.q = t.q; d.theta = t.theta; d.s = t.s;
         d.gy = t.gy; d.gx = t.gx; d.gs = t.gs; d.gtheta = t.gtheta;
-        d.partial = workspace ? (double *)(workspace + L.partial_off) + block : nullptr;
+        d.partial = workspace ? (double *)(workspace + L.partial_off) + unit : nullptr;
         d.slot = workspace ? (unsigned long long *)(workspace + L.counter_off) + slot : nullptr;
         d.inner = t.inner;
         d.slabs = p.slabs;
@@ -198,6 +243,7 @@ void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *wo
         d.block_begin = (unsigned)block;
         d.chan_begin = (unsigned)chan;
         d.sub = p.sub;
+        d.wave_units = p.waves ? 1u : 0u;
         d.dtype = t.dtype;
         d.lo = (float)t.qmin;
         d.hi = (float)t.qmax;
@@ -214,6 +260,7 @@ void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *wo
             d.adam_bc2 = (float)(1.0 - std::pow(a.beta2, (double)a.step));
         }
         block += p.blocks;
+        unit += p.units;
         chan += t.channels;
         slot += t.channels * (1 + (long long)p.sub);
     }
@@ -383,6 +430,21 @@ fq_status fq_validate(const fq_tensor *ts, int n, int mode)
     } catch (...) {
         return FQ_ERR_SHAPE;
     }
+}
+
+fq_status fq_layout(const fq_tensor *t, fq_layout_info *info)
+{
+    if (!t || !info) return FQ_ERR_NULL;
+    fq::Plan p;
+    fq_status st = fq::plan_tensor(*t, p, false);
+    if (st == FQ_OK && p.short_slabs && p.blocks >= (long long)fq::kWaveUnitsMinBlocks) st = fq::plan_tensor(*t, p, true);
+    if (st != FQ_OK) return st;
+    info->blocks = p.blocks;
+    info->units_per_channel = t->outer * (long long)p.cps;
+    info->unit_elems = p.chunk;
+    info->wave_units = p.waves ? 1 : 0;
+    info->extra_slots = (int32_t)p.sub;
+    return FQ_OK;
 }
 
 fq_status fq_workspace_init(void *workspace, size_t ws_bytes, void *hip_stream)

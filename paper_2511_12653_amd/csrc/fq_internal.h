@@ -9,9 +9,15 @@ namespace fq {
 constexpr int kBlock = 256;          // threads per block: four 64-wide wavefronts
 constexpr int kVecBytes = 16;        // one 128-bit global load/store per lane
 constexpr int kChunkVecs = 1280;     // at most this many 128-bit vectors per block (20 KiB)
+constexpr int kWaveChunkVecs = kChunkVecs / (kBlock / 64);   // what one wavefront covers: 320 vectors
 constexpr int kComputeUnits = 256;   // MI355X; used by the host to balance blocks over the chip
-constexpr unsigned kTicketFanIn = 64;   // more blocks than this per channel: tickets are drawn in two levels
-constexpr unsigned kTicketSubSlots = 32;
+// Units of a channel beyond kTicketFanIn draw their arrival tickets in two levels: that many
+// atomics on one address queue up at the memory-side atomic unit (60 units on one slot cost a
+// short-slab backward 17.4 us against 13.1 us with 16 first-level slots).
+constexpr unsigned kTicketFanIn = 16;
+constexpr unsigned kTicketSubSlots = 16;       // first-level slots per channel
+constexpr unsigned kTicketManyUnits = 256;     // beyond this many units per channel ...
+constexpr unsigned kTicketManySubSlots = 32;   // ... this many first-level slots
 constexpr unsigned kTreeBlocks = 4;      // up to this many blocks per channel combine by atomic exchange alone
 
 // Device-side view of one tensor.  Built on the host; passed as a kernel argument for
@@ -37,6 +43,8 @@ struct DevTensor {
     unsigned chunk;            // elements per chunk, a multiple of the vector width
     unsigned block_begin;      // first block of this tensor in the grid
     unsigned chan_begin;       // first channel of this tensor in the finalize grid
+    unsigned wave_units;       // 1: slabs are short, every wavefront owns one (cps = 1, chunk = the slab);
+                               // the tensor's blocks then number ceil(slabs / 4) and partial[] is per slab
     unsigned sub;              // extra slots per channel after the [channels] main ones: 0, 2 (pair slots of
                                // the exchange tree, 3 or 4 blocks per channel) or kTicketSubSlots
     int dtype;                 // 0 = FP16, 1 = FP32

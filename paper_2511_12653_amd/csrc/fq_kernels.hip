@@ -187,6 +187,10 @@ __device__ __forceinline__ float ste_terms(float x, const QParams &p, bool &in_r
     return r - (in_range ? v : 0.0f);
 }
 
+// Index of this wavefront in its block as a scalar: telling the compiler that it is uniform keeps
+// everything derived from it (the unit's slab, channel, pointers, loop bounds) in SGPRs.
+__device__ __forceinline__ unsigned wave_index() { return (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+
 // ---------------------------------------------------------------------------------------------
 // Chunk addressing shared by forward and backward.
 struct Chunk {
@@ -215,37 +219,34 @@ template <typename T> __device__ __forceinline__ int head_elems(const void *p, i
     return h < n ? h : n;
 }
 
-// Scale of this block's channel.  Callers issue their first global loads before this, so the
-// evaluation sits in the shadow of the memory latency.  FQ_SCALE_PER_WAVE = 1: every wavefront
-// evaluates Eq. (3)-(4) for itself (about a hundred binary64 instructions, no barrier, no LDS);
-// 0: one wavefront (rotating with the block index, so the work spreads over the four SIMDs of a
-// compute unit) evaluates it and the others read it from LDS after a barrier.
-#ifndef FQ_SCALE_PER_WAVE
-#define FQ_SCALE_PER_WAVE 0
-#endif
-template <bool NEED_SIGMOID>
+// Scale of this group's channel (G = 256: the block; G = 64: one wavefront).  Callers issue their
+// first global loads before this, so the evaluation sits in the shadow of the memory latency.
+// A block lets one wavefront (rotating with the block index, so the work spreads over the four
+// SIMDs of a compute unit) evaluate Eq. (3)-(4), about a hundred binary64 instructions, and the
+// others read it from LDS after a barrier; a lone wavefront evaluates it for itself.
+template <bool NEED_SIGMOID, int G>
 __device__ __forceinline__ QParams block_params(const DevTensor &d, float theta, BlockScale &bs)
 {
-#if FQ_SCALE_PER_WAVE
-    const Scale sc = compute_scale<NEED_SIGMOID>(theta, d.eps, d.s_min, d.s_max);
-    bs.s = sc.s;
-    bs.rd = 1.0 / (double)sc.s;
-    bs.sigmoid = sc.sigmoid;
-    bs.clip_active = sc.clip_active ? 1u : 0u;
-#else
-    __shared__ BlockScale shared_scale;
-    if ((threadIdx.x >> 6) == (blockIdx.x & (kBlock / 64 - 1))) {
+    if (G == 64) {
         const Scale sc = compute_scale<NEED_SIGMOID>(theta, d.eps, d.s_min, d.s_max);
-        if ((threadIdx.x & 63) == 0) {
-            shared_scale.s = sc.s;
-            shared_scale.rd = 1.0 / (double)sc.s;
-            shared_scale.sigmoid = sc.sigmoid;
-            shared_scale.clip_active = sc.clip_active ? 1u : 0u;
+        bs.s = sc.s;
+        bs.rd = 1.0 / (double)sc.s;
+        bs.sigmoid = sc.sigmoid;
+        bs.clip_active = sc.clip_active ? 1u : 0u;
+    } else {
+        __shared__ BlockScale shared_scale;
+        if ((threadIdx.x >> 6) == (blockIdx.x & (kBlock / 64 - 1))) {
+            const Scale sc = compute_scale<NEED_SIGMOID>(theta, d.eps, d.s_min, d.s_max);
+            if ((threadIdx.x & 63) == 0) {
+                shared_scale.s = sc.s;
+                shared_scale.rd = 1.0 / (double)sc.s;
+                shared_scale.sigmoid = sc.sigmoid;
+                shared_scale.clip_active = sc.clip_active ? 1u : 0u;
+            }
         }
+        __syncthreads();
+        bs = shared_scale;
     }
-    __syncthreads();
-    bs = shared_scale;
-#endif
     QParams p;
     p.rd = bs.rd;
     p.s = bs.s;
@@ -268,17 +269,17 @@ __device__ __forceinline__ void forward_elem(const T *x, T *y, int8_t *q, int i,
 
 // WRITE_Y: write the dequantized tensor y.  EMIT_Q: write the int8 codes, N per lane packed into
 // one 64-bit (FP16 input) or 32-bit (FP32 input) store.  At least one of the two.
-template <typename T, bool WRITE_Y, bool EMIT_Q>
-__device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local_block)
+template <typename T, bool WRITE_Y, bool EMIT_Q, int G>
+__device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned unit)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
     typedef unsigned QV __attribute__((ext_vector_type(N / 4)));
-    const Chunk ck = locate_chunk(d, local_block);
+    const Chunk ck = locate_chunk(d, unit);
     const T *x = (const T *)d.x + ck.first;
     T *y = WRITE_Y ? (T *)d.y + ck.first : nullptr;
     int8_t *q = EMIT_Q ? d.q + ck.first : nullptr;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & (G - 1);
     const float theta = ld_uniform(d.theta + ck.channel);
 
     const bool vector_ok = !WRITE_Y || (((uintptr_t)x ^ (uintptr_t)y) & (kVecBytes - 1)) == 0;
@@ -295,19 +296,19 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
         const int last = nvec - 1;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            int v = u * kBlock + tid;
+            int v = u * G + tid;
             r[u] = ld_stream(xv + (v < last ? v : last));
         }
     }
 
     BlockScale bs;
-    const QParams p = block_params<false>(d, theta, bs);
+    const QParams p = block_params<false, G>(d, theta, bs);
     if (d.s && ck.first == (long long)ck.channel * d.inner && tid == 0) st_global(d.s + ck.channel, p.s);
 
     for (int v0 = 0; v0 < nvec;) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            int v = v0 + u * kBlock + tid;
+            int v = v0 + u * G + tid;
             if (v < nvec) {
                 float quot[N];
 #pragma unroll
@@ -335,29 +336,42 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned local
                 }
             }
         }
-        v0 += kUnroll * kBlock;
+        v0 += kUnroll * G;
         if (v0 >= nvec) break;
         const int last = nvec - 1;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            int v = v0 + u * kBlock + tid;
+            int v = v0 + u * G + tid;
             r[u] = ld_stream(xv + (v < last ? v : last));
         }
     }
 
     // scalar head (before the first 16-byte boundary, or the whole chunk if x and y are
     // misaligned relative to each other) and tail (after the last whole vector)
-    for (int i = tid; i < head; i += kBlock) forward_elem<T, WRITE_Y, EMIT_Q>(x, y, q, i, p);
-    for (int i = head + nvec * N + tid; i < ck.n; i += kBlock) forward_elem<T, WRITE_Y, EMIT_Q>(x, y, q, i, p);
+    for (int i = tid; i < head; i += G) forward_elem<T, WRITE_Y, EMIT_Q>(x, y, q, i, p);
+    for (int i = head + nvec * N + tid; i < ck.n; i += G) forward_elem<T, WRITE_Y, EMIT_Q>(x, y, q, i, p);
 }
 
 // what one tensor asks of the forward pass: y only, y and codes, or codes only
+template <typename T, int G>
+__device__ __forceinline__ void forward_variants(const DevTensor &d, unsigned unit)
+{
+    if (!d.q) forward_chunk<T, true, false, G>(d, unit);
+    else if (d.y) forward_chunk<T, true, true, G>(d, unit);
+    else forward_chunk<T, false, true, G>(d, unit);
+}
+
+// Tensors whose slabs are short (d.wave_units) give every wavefront a slab of its own: four
+// slabs to a block, no barrier.  Otherwise the block owns one chunk.
 template <typename T>
 __device__ __forceinline__ void forward_dispatch(const DevTensor &d, unsigned local_block)
 {
-    if (!d.q) forward_chunk<T, true, false>(d, local_block);
-    else if (d.y) forward_chunk<T, true, true>(d, local_block);
-    else forward_chunk<T, false, true>(d, local_block);
+    if (d.wave_units) {
+        const unsigned unit = local_block * (kBlock / 64) + wave_index();
+        if (unit < d.slabs * d.cps) forward_variants<T, 64>(d, unit);
+    } else {
+        forward_variants<T, kBlock>(d, local_block);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -377,7 +391,7 @@ __device__ __forceinline__ double backward_elem(const T *x, const T *gy, T *gx, 
 }
 
 // Per-thread sum of gy*t over this thread's elements of the chunk (binary64).
-template <typename T, bool WRITE_GX>
+template <typename T, bool WRITE_GX, int G>
 __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk &ck, BlockScale &bs)
 {
     typedef typename VecOf<T>::type VT;
@@ -385,7 +399,7 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
     const T *x = (const T *)d.x + ck.first;
     const T *gy = (const T *)d.gy + ck.first;
     T *gx = WRITE_GX ? (T *)d.gx + ck.first : nullptr;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & (G - 1);
     const float theta = ld_uniform(d.theta + ck.channel);
 
     uintptr_t mis = (uintptr_t)x ^ (uintptr_t)gy;
@@ -402,14 +416,14 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
         const int last = nvec - 1;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            int v = u * kBlock + tid;
+            int v = u * G + tid;
             v = v < last ? v : last;
             rx[u] = ld_stream(xv + v);
             rg[u] = ld_stream(gv + v);
         }
     }
 
-    const QParams p = block_params<true>(d, theta, bs);
+    const QParams p = block_params<true, G>(d, theta, bs);
 
     double acc[kUnroll];
 #pragma unroll
@@ -418,7 +432,7 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
     for (int v0 = 0; v0 < nvec;) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            int v = v0 + u * kBlock + tid;
+            int v = v0 + u * G + tid;
             if (v < nvec) {
                 VT o;
                 bool any_nan = false;
@@ -434,12 +448,12 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
                 if (WRITE_GX) st_stream(ov + v, o);
             }
         }
-        v0 += kUnroll * kBlock;
+        v0 += kUnroll * G;
         if (v0 >= nvec) break;
         const int last = nvec - 1;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            int v = v0 + u * kBlock + tid;
+            int v = v0 + u * G + tid;
             v = v < last ? v : last;
             rx[u] = ld_stream(xv + v);
             rg[u] = ld_stream(gv + v);
@@ -449,8 +463,8 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
     double sum = 0.0;
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) sum += acc[u];
-    for (int i = tid; i < head; i += kBlock) sum = backward_elem<T, WRITE_GX>(x, gy, gx, i, p, sum);
-    for (int i = head + nvec * N + tid; i < ck.n; i += kBlock)
+    for (int i = tid; i < head; i += G) sum = backward_elem<T, WRITE_GX>(x, gy, gx, i, p, sum);
+    for (int i = head + nvec * N + tid; i < ck.n; i += G)
         sum = backward_elem<T, WRITE_GX>(x, gy, gx, i, p, sum);
     return sum;
 }
@@ -518,21 +532,142 @@ __device__ __forceinline__ void finalize_channel(const DevTensor &d, unsigned c,
     __syncthreads();
 }
 
-// One block of the backward grid.
-//
-// How the blocks of a channel combine their sums (FUSED; no float atomics, fixed order):
-//   1 block per channel   the block writes the channel's gradients itself;
-//   2 blocks per channel  each swaps its sum into the channel's 64-bit slot; the one that finds
+// value of v in the given lane, as a wavefront-uniform scalar
+__device__ __forceinline__ double read_lane(double v, int lane)
+{
+    const unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)bits, lane);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(bits >> 32), lane);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+
+// The same sum, bit for bit, by a single wavefront (for tensors whose units are wavefronts): the
+// block-wide version gives thread t the sums t, t+256, ... and adds wavefront 0's tree to
+// wavefront 1's, 2's and 3's in that order; here the one wavefront plays the four in turn.
+__device__ __forceinline__ void finalize_channel_wave(const DevTensor &d, unsigned c, const BlockScale &bs)
+{
+    const unsigned bpc = d.outer * d.cps;
+    const unsigned lane = threadIdx.x & 63;
+    double total = 0.0;
+    for (unsigned w = 0; w < kBlock / 64; ++w) {
+        double acc = 0.0;
+        for (unsigned j = w * 64 + lane; j < bpc; j += kBlock) {
+            const unsigned o = j / d.cps;
+            const unsigned k = j - o * d.cps;
+            const size_t idx = ((size_t)o * d.channels + c) * d.cps + k;
+            acc += __hip_atomic_load(&d.partial[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        acc = wave_sum(acc);
+        total += read_lane(acc, kSumLane);
+    }
+    if (lane == kSumLane) write_channel_grads(d, c, total, bs);
+}
+
+// How the units (blocks, or wavefronts of short-slab tensors) of a channel combine their sums
+// (FUSED; no float atomics, fixed order):
+//   1 unit per channel    the unit writes the channel's gradients itself;
+//   2 units per channel   each swaps its sum into the channel's 64-bit slot; the one that finds
 //                         its partner's sum there adds the two (a+b = b+a) and clears the slot:
 //                         one atomic round trip, the payload travels in the atomic itself;
 //   3 or 4                two rounds of that exchange, pairs first (two more slots per channel);
-//   more                  each block stores its sum, waits for that store, then draws a ticket
-//                         from the slot; the block with the last ticket re-reads all sums in index
-//                         order and clears the slot.  Beyond kTicketFanIn blocks per channel the
-//                         tickets are drawn in two levels (kTicketSubSlots first-level slots).
-// The slot is zero between calls.  (A sum of +0.0 is swapped in as -0.0 so that it differs from
+//   more                  each unit stores its sum, waits for that store, then draws a ticket
+//                         from the slot; the unit with the last ticket has all sums re-read in
+//                         index order and clears the slot.  Beyond kTicketFanIn units per channel
+//                         the tickets are drawn in two levels (d.sub first-level slots).
+// The slots are zero between calls.  (A sum of +0.0 is swapped in as -0.0 so that it differs from
 // an empty slot; it adds the same.)
 // Without FUSED the sums are only stored and finalize_kernel adds them in a second launch.
+//
+// Called by one lane per unit with the unit's total.  Returns 1 if the caller drew the last
+// ticket, i.e. its block must now run finalize_channel for ck.channel.
+template <bool FUSED>
+__device__ __forceinline__ unsigned combine(const DevTensor &d, const Chunk &ck, unsigned unit, double total,
+                                            const BlockScale &bs)
+{
+    const unsigned bpc = d.outer * d.cps;
+    unsigned last = 0u;
+    if (!FUSED) {
+        __hip_atomic_store(&d.partial[unit], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (bpc == 1u) {
+        write_channel_grads(d, ck.channel, total, bs);
+    } else if (bpc == 2u) {
+        unsigned long long mine = __builtin_bit_cast(unsigned long long, total);
+        if (mine == 0ull) mine = 0x8000000000000000ull;
+        const unsigned long long theirs = __hip_atomic_exchange(&d.slot[ck.channel], mine, __ATOMIC_RELAXED,
+                                                                __HIP_MEMORY_SCOPE_AGENT);
+        if (theirs != 0ull) {
+            __hip_atomic_store(&d.slot[ck.channel], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const double both = (__builtin_bit_cast(double, theirs) + total) + 0.0;
+            write_channel_grads(d, ck.channel, both, bs);
+        }
+    } else if (bpc <= kTreeBlocks) {
+        // Three or four units: two rounds of the same exchange, associated as finalize_channel
+        // associates its sums, (p0 + p1) + (p2 + p3) with an absent p3 counting as +0.0, so the
+        // bits equal those of the two-launch mode.  Unlike the tickets below this needs no wait
+        // for the unit's own gx stores and no re-read of the partial sums.
+        const unsigned o = ck.slab / d.channels;
+        const unsigned j = o * d.cps + (unit - ck.slab * d.cps);
+        double pair_sum = total + 0.0;                 // unit 2 of 3 has no partner
+        bool carry_on = true;
+        if (!(bpc == 3u && j == 2u)) {
+            unsigned long long *pair = d.slot + d.channels + (size_t)ck.channel * 2u + (j >> 1);
+            unsigned long long mine = __builtin_bit_cast(unsigned long long, total);
+            if (mine == 0ull) mine = 0x8000000000000000ull;
+            const unsigned long long theirs = __hip_atomic_exchange(pair, mine, __ATOMIC_RELAXED,
+                                                                    __HIP_MEMORY_SCOPE_AGENT);
+            carry_on = theirs != 0ull;
+            if (carry_on) {
+                __hip_atomic_store(pair, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pair_sum = __builtin_bit_cast(double, theirs) + total;
+            }
+        }
+        if (carry_on) {
+            unsigned long long mine = __builtin_bit_cast(unsigned long long, pair_sum);
+            if (mine == 0ull) mine = 0x8000000000000000ull;
+            const unsigned long long theirs = __hip_atomic_exchange(&d.slot[ck.channel], mine, __ATOMIC_RELAXED,
+                                                                    __HIP_MEMORY_SCOPE_AGENT);
+            if (theirs != 0ull) {
+                __hip_atomic_store(&d.slot[ck.channel], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const double all = (__builtin_bit_cast(double, theirs) + pair_sum) + 0.0;
+                write_channel_grads(d, ck.channel, all, bs);
+            }
+        }
+    } else {
+        // Agent-scope store: written through to where every XCD can see it.  Wait until it
+        // has completed, then take a ticket.  Only the partial has to be published, so no
+        // cache write-back of the unit's gx stores is requested (a full agent-scope release
+        // would flush the whole L2 once per block).
+        __hip_atomic_store(&d.partial[unit], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        unsigned long long *top = &d.slot[ck.channel];
+        unsigned long long expected = bpc;
+        bool draw_top = true;
+        if (d.sub) {
+            // Hundreds of units drawing from one address queue up behind each other at the
+            // memory-side atomic unit.  Unit j of the channel draws from sub-slot j mod sub
+            // first; only the last arrival there goes on to the channel's own slot.
+            const unsigned o = ck.slab / d.channels;
+            const unsigned j = o * d.cps + (unit - ck.slab * d.cps);
+            const unsigned k = j % d.sub;
+            const unsigned long long arrivals = (bpc - k + d.sub - 1u) / d.sub;
+            unsigned long long *first = d.slot + d.channels + (size_t)ck.channel * d.sub + k;
+            const unsigned long long t1 = __hip_atomic_fetch_add(first, 1ull, __ATOMIC_RELAXED,
+                                                                 __HIP_MEMORY_SCOPE_AGENT);
+            draw_top = t1 == arrivals - 1ull;
+            if (draw_top) __hip_atomic_store(first, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            expected = d.sub;                      // bpc > sub, so every sub-slot is in use
+        }
+        if (draw_top) {
+            const unsigned long long ticket = __hip_atomic_fetch_add(top, 1ull, __ATOMIC_RELAXED,
+                                                                     __HIP_MEMORY_SCOPE_AGENT);
+            last = (ticket == expected - 1ull) ? 1u : 0u;
+            if (last) __hip_atomic_store(top, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    return last;
+}
+
+// One block of the backward grid, owning one chunk of one slab.
 template <typename T, bool FUSED>
 __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned local_block)
 {
@@ -543,98 +678,18 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
     const Chunk ck = locate_chunk(d, local_block);
     const bool write_gx = !(d.flags & 1u);
     BlockScale bs;
-    double sum = write_gx ? backward_chunk<T, true>(d, ck, bs) : backward_chunk<T, false>(d, ck, bs);
+    double sum = write_gx ? backward_chunk<T, true, kBlock>(d, ck, bs) : backward_chunk<T, false, kBlock>(d, ck, bs);
 
     sum = wave_sum(sum);
     if ((threadIdx.x & 63) == kSumLane) wave_part[threadIdx.x >> 6] = sum;
     __syncthreads();
-    const unsigned bpc = d.outer * d.cps;
     if (threadIdx.x == 0) {
         double total = 0.0;
 #pragma unroll
         for (int w = 0; w < kBlock / 64; ++w) total += wave_part[w];
-        unsigned last = 0u;
-        if (!FUSED) {
-            __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else if (bpc == 1u) {
-            write_channel_grads(d, ck.channel, total, bs);
-        } else if (bpc == 2u) {
-            unsigned long long mine = __builtin_bit_cast(unsigned long long, total);
-            if (mine == 0ull) mine = 0x8000000000000000ull;
-            const unsigned long long theirs = __hip_atomic_exchange(&d.slot[ck.channel], mine, __ATOMIC_RELAXED,
-                                                                    __HIP_MEMORY_SCOPE_AGENT);
-            if (theirs != 0ull) {
-                __hip_atomic_store(&d.slot[ck.channel], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const double both = (__builtin_bit_cast(double, theirs) + total) + 0.0;
-                write_channel_grads(d, ck.channel, both, bs);
-            }
-        } else if (bpc <= kTreeBlocks) {
-            // Three or four blocks: two rounds of the same exchange, associated as finalize_channel
-            // associates its sums, (p0 + p1) + (p2 + p3) with an absent p3 counting as +0.0, so the
-            // bits equal those of the two-launch mode.  Unlike the tickets below this needs no wait
-            // for the block's own gx stores and no re-read of the partial sums.
-            const unsigned o = ck.slab / d.channels;
-            const unsigned j = o * d.cps + (local_block - ck.slab * d.cps);
-            double pair_sum = total + 0.0;                 // block 2 of 3 has no partner
-            bool carry_on = true;
-            if (!(bpc == 3u && j == 2u)) {
-                unsigned long long *pair = d.slot + d.channels + (size_t)ck.channel * 2u + (j >> 1);
-                unsigned long long mine = __builtin_bit_cast(unsigned long long, total);
-                if (mine == 0ull) mine = 0x8000000000000000ull;
-                const unsigned long long theirs = __hip_atomic_exchange(pair, mine, __ATOMIC_RELAXED,
-                                                                        __HIP_MEMORY_SCOPE_AGENT);
-                carry_on = theirs != 0ull;
-                if (carry_on) {
-                    __hip_atomic_store(pair, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    pair_sum = __builtin_bit_cast(double, theirs) + total;
-                }
-            }
-            if (carry_on) {
-                unsigned long long mine = __builtin_bit_cast(unsigned long long, pair_sum);
-                if (mine == 0ull) mine = 0x8000000000000000ull;
-                const unsigned long long theirs = __hip_atomic_exchange(&d.slot[ck.channel], mine, __ATOMIC_RELAXED,
-                                                                        __HIP_MEMORY_SCOPE_AGENT);
-                if (theirs != 0ull) {
-                    __hip_atomic_store(&d.slot[ck.channel], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    const double all = (__builtin_bit_cast(double, theirs) + pair_sum) + 0.0;
-                    write_channel_grads(d, ck.channel, all, bs);
-                }
-            }
-        } else {
-            // Agent-scope store: written through to where every XCD can see it.  Wait until it
-            // has completed, then take a ticket.  Only the partial has to be published, so no
-            // cache write-back of the block's gx stores is requested (a full agent-scope release
-            // would flush the whole L2 once per block).
-            __hip_atomic_store(&d.partial[local_block], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            unsigned long long *top = &d.slot[ck.channel];
-            unsigned long long expected = bpc;
-            bool draw_top = true;
-            if (d.sub) {
-                // Hundreds of blocks drawing from one address queue up behind each other at the
-                // memory-side atomic unit.  Block j of the channel draws from sub-slot j mod sub
-                // first; only the last arrival there goes on to the channel's own slot.
-                const unsigned o = ck.slab / d.channels;
-                const unsigned j = o * d.cps + (local_block - ck.slab * d.cps);
-                const unsigned k = j % d.sub;
-                const unsigned long long arrivals = (bpc - k + d.sub - 1u) / d.sub;
-                unsigned long long *first = d.slot + d.channels + (size_t)ck.channel * d.sub + k;
-                const unsigned long long t1 = __hip_atomic_fetch_add(first, 1ull, __ATOMIC_RELAXED,
-                                                                     __HIP_MEMORY_SCOPE_AGENT);
-                draw_top = t1 == arrivals - 1ull;
-                if (draw_top) __hip_atomic_store(first, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                expected = d.sub;                      // bpc > sub, so every sub-slot is in use
-            }
-            if (draw_top) {
-                const unsigned long long ticket = __hip_atomic_fetch_add(top, 1ull, __ATOMIC_RELAXED,
-                                                                         __HIP_MEMORY_SCOPE_AGENT);
-                last = (ticket == expected - 1ull) ? 1u : 0u;
-                if (last) __hip_atomic_store(top, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        is_last = last;
+        is_last = combine<FUSED>(d, ck, local_block, total, bs);
     }
-    if (FUSED && bpc > kTreeBlocks) {
+    if (FUSED && d.outer * d.cps > kTreeBlocks) {
         __syncthreads();
         if (is_last) {
             // every other block of this channel completed its partial store before its ticket
@@ -642,6 +697,37 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, unsigned loca
             finalize_channel(d, ck.channel, bs, fin_part);
         }
     }
+}
+
+// One block of the backward grid for a tensor with short slabs: every wavefront owns a slab (a
+// unit) of its own -- scale, sum, combination and, if it draws the last ticket of its channel,
+// the final sum, all per wavefront; the block never meets at a barrier.
+template <typename T, bool FUSED>
+__device__ __forceinline__ void backward_waves(const DevTensor &d, unsigned local_block)
+{
+    const unsigned unit = local_block * (kBlock / 64) + wave_index();
+    if (unit >= d.slabs * d.cps) return;
+    const bool write_gx = !(d.flags & 1u);
+    const Chunk ck = locate_chunk(d, unit);
+    BlockScale bs;
+    double sum = write_gx ? backward_chunk<T, true, 64>(d, ck, bs) : backward_chunk<T, false, 64>(d, ck, bs);
+    sum = wave_sum(sum);
+    unsigned last = 0u;
+    if ((threadIdx.x & 63) == kSumLane) last = combine<FUSED>(d, ck, unit, sum, bs);
+    if (FUSED && d.outer * d.cps > kTreeBlocks) {
+        if (__builtin_amdgcn_readlane((int)last, kSumLane)) {
+            // every other unit of this channel completed its partial store before its ticket
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            finalize_channel_wave(d, ck.channel, bs);
+        }
+    }
+}
+
+template <typename T, bool FUSED>
+__device__ __forceinline__ void backward_dispatch(const DevTensor &d, unsigned local_block)
+{
+    if (d.wave_units) backward_waves<T, FUSED>(d, local_block);
+    else backward_block<T, FUSED>(d, local_block);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -680,10 +766,16 @@ __device__ __forceinline__ DevTensor fetch(const DevTensor *table, int i)
 }
 
 // Single tensor: descriptor in the kernel arguments (SGPRs), dtype fixed at compile time.
-template <typename T, bool WRITE_Y, bool EMIT_Q>
+// WAVES: the tensor's slabs are short and every wavefront owns one (chosen by the launcher).
+template <typename T, bool WRITE_Y, bool EMIT_Q, bool WAVES>
 __global__ void __launch_bounds__(kBlock) forward_kernel(const DevTensor d)
 {
-    forward_chunk<T, WRITE_Y, EMIT_Q>(d, blockIdx.x);
+    if (WAVES) {
+        const unsigned unit = blockIdx.x * (kBlock / 64) + wave_index();
+        if (unit < d.slabs * d.cps) forward_chunk<T, WRITE_Y, EMIT_Q, 64>(d, unit);
+    } else {
+        forward_chunk<T, WRITE_Y, EMIT_Q, kBlock>(d, blockIdx.x);
+    }
 }
 
 // ANY_Q = false: no tensor of the list wants codes (the usual case; keeps the kernel lean)
@@ -696,15 +788,25 @@ __global__ void __launch_bounds__(kBlock) forward_multi_kernel(const DevTensor *
         if (d.dtype == 0) forward_dispatch<_Float16>(d, local);
         else forward_dispatch<float>(d, local);
     } else {
-        if (d.dtype == 0) forward_chunk<_Float16, true, false>(d, local);
-        else forward_chunk<float, true, false>(d, local);
+        if (d.wave_units) {
+            const unsigned unit = local * (kBlock / 64) + wave_index();
+            if (unit < d.slabs * d.cps) {
+                if (d.dtype == 0) forward_chunk<_Float16, true, false, 64>(d, unit);
+                else forward_chunk<float, true, false, 64>(d, unit);
+            }
+        } else if (d.dtype == 0) {
+            forward_chunk<_Float16, true, false, kBlock>(d, local);
+        } else {
+            forward_chunk<float, true, false, kBlock>(d, local);
+        }
     }
 }
 
-template <typename T, bool FUSED>
+template <typename T, bool FUSED, bool WAVES>
 __global__ void __launch_bounds__(kBlock) backward_kernel(const DevTensor d)
 {
-    backward_block<T, FUSED>(d, blockIdx.x);
+    if (WAVES) backward_waves<T, FUSED>(d, blockIdx.x);
+    else backward_block<T, FUSED>(d, blockIdx.x);
 }
 
 template <bool FUSED>
@@ -712,8 +814,8 @@ __global__ void __launch_bounds__(kBlock) backward_multi_kernel(const DevTensor 
 {
     const DevTensor d = fetch(table, find_by_block((const FQ_CONST DevTensor *)table, n, blockIdx.x));
     const unsigned local = blockIdx.x - d.block_begin;
-    if (d.dtype == 0) backward_block<_Float16, FUSED>(d, local);
-    else backward_block<float, FUSED>(d, local);
+    if (d.dtype == 0) backward_dispatch<_Float16, FUSED>(d, local);
+    else backward_dispatch<float, FUSED>(d, local);
 }
 
 // one block per channel: second pass of the two-pass backward, and the whole backward of tensors
@@ -725,7 +827,7 @@ __global__ void __launch_bounds__(kBlock) finalize_kernel(const KArgs a)
                                 : a.one;
     const unsigned c = blockIdx.x - d.chan_begin;
     BlockScale bs;
-    block_params<true>(d, ld_uniform(d.theta + c), bs);
+    block_params<true, kBlock>(d, ld_uniform(d.theta + c), bs);
     finalize_channel(d, c, bs, fin_part);
 }
 
@@ -756,12 +858,12 @@ static void launch(K kernel, unsigned blocks, hipStream_t st, Args... args)
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kBlock), 0, st, args...);
 }
 
-template <typename T>
+template <typename T, bool WAVES>
 static void launch_forward_single(const DevTensor &d, unsigned blocks, hipStream_t st)
 {
-    if (!d.q) launch(forward_kernel<T, true, false>, blocks, st, d);
-    else if (d.y) launch(forward_kernel<T, true, true>, blocks, st, d);
-    else launch(forward_kernel<T, false, true>, blocks, st, d);
+    if (!d.q) launch(forward_kernel<T, true, false, WAVES>, blocks, st, d);
+    else if (d.y) launch(forward_kernel<T, true, true, WAVES>, blocks, st, d);
+    else launch(forward_kernel<T, false, true, WAVES>, blocks, st, d);
 }
 
 int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream)
@@ -771,11 +873,31 @@ int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream)
         if (emit_q) launch(forward_multi_kernel<true>, blocks, st, a.table, a.n);
         else launch(forward_multi_kernel<false>, blocks, st, a.table, a.n);
     } else if (a.one.dtype == 0) {
-        launch_forward_single<_Float16>(a.one, blocks, st);
+        if (a.one.wave_units) launch_forward_single<_Float16, true>(a.one, blocks, st);
+        else launch_forward_single<_Float16, false>(a.one, blocks, st);
     } else {
-        launch_forward_single<float>(a.one, blocks, st);
+        if (a.one.wave_units) launch_forward_single<float, true>(a.one, blocks, st);
+        else launch_forward_single<float, false>(a.one, blocks, st);
     }
     return (int)hipGetLastError();
+}
+
+template <typename T, bool WAVES>
+static void launch_backward_typed(const DevTensor &d, unsigned blocks, bool fused_finalize, hipStream_t st)
+{
+    if (fused_finalize) launch(backward_kernel<T, true, WAVES>, blocks, st, d);
+    else launch(backward_kernel<T, false, WAVES>, blocks, st, d);
+}
+
+static void launch_backward_single(const DevTensor &d, unsigned blocks, bool fused_finalize, hipStream_t st)
+{
+    if (d.dtype == 0) {
+        if (d.wave_units) launch_backward_typed<_Float16, true>(d, blocks, fused_finalize, st);
+        else launch_backward_typed<_Float16, false>(d, blocks, fused_finalize, st);
+    } else {
+        if (d.wave_units) launch_backward_typed<float, true>(d, blocks, fused_finalize, st);
+        else launch_backward_typed<float, false>(d, blocks, fused_finalize, st);
+    }
 }
 
 int launch_backward(const KArgs &a, unsigned blocks, bool fused_finalize, void *stream)
@@ -784,12 +906,8 @@ int launch_backward(const KArgs &a, unsigned blocks, bool fused_finalize, void *
     if (a.table) {
         if (fused_finalize) launch(backward_multi_kernel<true>, blocks, st, a.table, a.n);
         else launch(backward_multi_kernel<false>, blocks, st, a.table, a.n);
-    } else if (a.one.dtype == 0) {
-        if (fused_finalize) launch(backward_kernel<_Float16, true>, blocks, st, a.one);
-        else launch(backward_kernel<_Float16, false>, blocks, st, a.one);
     } else {
-        if (fused_finalize) launch(backward_kernel<float, true>, blocks, st, a.one);
-        else launch(backward_kernel<float, false>, blocks, st, a.one);
+        launch_backward_single(a.one, blocks, fused_finalize, st);
     }
     return (int)hipGetLastError();
 }

@@ -25,7 +25,7 @@ def test_exports_every_declared_symbol(fq):
     assert set(names) >= {"fq_forward", "fq_backward", "fq_multi_tensor", "fq_workspace_bytes",
                           "fq_validate", "fq_status_string", "fq_workspace_init", "fq_plan_create",
                           "fq_plan_run", "fq_plan_run_adam", "fq_plan_destroy",
-                          "fq_distill_loss", "fq_distill_workspace_bytes"}
+                          "fq_distill_loss", "fq_distill_workspace_bytes", "fq_layout"}
     lib = ctypes.CDLL(fq.library_path())
     for n in set(names):
         assert getattr(lib, n) is not None
@@ -108,17 +108,23 @@ def test_workspace_bytes(fq):
     fwd = fq.fq_workspace_bytes(t, 1)
     bwd = fq.fq_workspace_bytes(t, 2)
     assert fwd % 256 == 0 and bwd % 256 == 0 and fwd >= 256
-    assert bwd >= fwd + 3840 * 8 + 128 * 8
-    assert bwd <= fwd + 3840 * 8 + 128 * 8 + 3 * 256
+    # 30 blocks per channel: more than 16, so each channel has 16 first-level ticket slots beside its own
+    assert bwd >= fwd + 3840 * 8 + 128 * 17 * 8
+    assert bwd <= fwd + 3840 * 8 + 128 * 17 * 8 + 3 * 256
     # one scale for 7 372 800 FP16 elements = 921 600 vectors: 720 blocks of 1280 vectors share the
     # channel, more than 64, so it gets 32 first-level ticket slots beside its own: 33 slots
     pt = _desc(fq, outer=1, channels=1, inner=7372800, x=1 << 32, y=2 << 32, gy=3 << 32, gx=4 << 32)
     assert fq.fq_workspace_bytes(pt, 2) == fq.fq_workspace_bytes(pt, 1) + (720 * 8 + 128) + 512
-    # 64 blocks per channel still share one slot
-    few = _desc(fq, outer=32, channels=3, inner=19200, x=1 << 32, y=2 << 32, gy=3 << 32, gx=4 << 32)
-    assert fq.fq_workspace_bytes(few, 2) == fq.fq_workspace_bytes(few, 1) + 32 * 3 * 2 * 8 + 256
+    # 16 blocks per channel still share one slot; 18 get 16 first-level slots each
+    few = _desc(fq, outer=8, channels=384, inner=19200, x=1 << 32, y=2 << 32, gy=3 << 32, gx=4 << 32)
+    assert fq.fq_workspace_bytes(few, 2) == fq.fq_workspace_bytes(few, 1) + 8 * 384 * 2 * 8 + 384 * 8
+    more = _desc(fq, outer=9, channels=384, inner=19200, x=1 << 32, y=2 << 32, gy=3 << 32, gx=4 << 32)
+    assert fq.fq_workspace_bytes(more, 2) == fq.fq_workspace_bytes(more, 1) + 9 * 384 * 2 * 8 + 384 * 17 * 8
+    # short slabs (100 FP16 elements): one wavefront per slab, one partial per slab, 2 blocks for 6 slabs
+    short = _desc(fq, outer=2, channels=3, inner=100)
+    assert fq.fq_workspace_bytes(short, 2) == fq.fq_workspace_bytes(short, 1) + 256 + 256
     two = fq.fq_workspace_bytes([t, t], 2)
-    assert two >= 2 * (3840 * 8 + 128 * 8)
+    assert two >= 2 * (3840 * 8 + 128 * 17 * 8)
     assert fq.fq_workspace_bytes([], 2) == 256
     # launching calls refuse a missing or short workspace before touching the GPU
     with pytest.raises(b.FqError) as e:
@@ -196,3 +202,42 @@ def test_codes_may_not_share_memory_with_x_or_y(fq):
         d = _desc(fq, x=0x1000, y=0x2000, **kw)
         assert fq.fq_validate(d, fq.FQ_MODE_FORWARD) == -9
     assert fq.fq_validate(_desc(fq, x=0x1000, y=0x2000, q=0x3000), fq.FQ_MODE_FORWARD) == 0
+
+
+def test_layout_info(fq):
+    big = dict(x=1 << 32, y=2 << 32, gy=3 << 32, gx=4 << 32)
+    # the headline tensor: 2 blocks of 1200 vectors per slab, exchange between the two
+    i = fq.fq_layout(_desc(fq, outer=1, channels=384, inner=19200, **big))
+    assert (i.blocks, i.units_per_channel, i.unit_elems, i.wave_units, i.extra_slots) == (768, 2, 9600, 0, 0)
+    # a 188 x 120 map: four blocks per channel, the exchange tree with its two pair slots
+    i = fq.fq_layout(_desc(fq, outer=1, channels=384, inner=22560, **big))
+    assert (i.units_per_channel, i.wave_units, i.extra_slots) == (4, 0, 2)
+    # 15 frames: 30 blocks per channel, two-level tickets with 16 first-level slots
+    i = fq.fq_layout(_desc(fq, outer=15, channels=128, inner=19200, **big))
+    assert (i.blocks, i.units_per_channel, i.extra_slots) == (3840, 30, 16)
+    # one scale for everything: 720 blocks, 32 first-level slots
+    i = fq.fq_layout(_desc(fq, outer=1, channels=1, inner=7372800, **big))
+    assert (i.blocks, i.units_per_channel, i.extra_slots) == (720, 720, 32)
+    # short slabs: a wavefront per slab (30 x 40 FP16 = 150 vectors), units per channel = outer
+    i = fq.fq_layout(_desc(fq, outer=15, channels=384, inner=1200, **big))
+    assert (i.blocks, i.units_per_channel, i.unit_elems, i.wave_units, i.extra_slots) == (1440, 15, 1200, 1, 0)
+    # the same short slabs in a small tensor: a block per slab (the launch has no blocks to spare)
+    i = fq.fq_layout(_desc(fq, outer=3, channels=5, inner=1000, **big))
+    assert (i.blocks, i.units_per_channel, i.wave_units, i.extra_slots) == (15, 3, 0, 2)
+    assert fq.fq_layout(_desc(fq, outer=1, channels=4095, inner=1000, **big)).wave_units == 0
+    assert fq.fq_layout(_desc(fq, outer=1, channels=4096, inner=1000, **big)).wave_units == 1
+    # 319 vectors still go to one wavefront, 320 do not (one vector is kept for a misaligned head)
+    assert fq.fq_layout(_desc(fq, outer=1, channels=5000, inner=319 * 8, **big)).wave_units == 1
+    assert fq.fq_layout(_desc(fq, outer=1, channels=5000, inner=320 * 8, **big)).wave_units == 0
+    # in a list the switch follows the whole launch: the small tensor rides along with a large one
+    small = _desc(fq, outer=3, channels=5, inner=1000, **big)
+    large = _desc(fq, outer=15, channels=128, inner=19200, **big)
+    alone = fq.fq_workspace_bytes([small], 2)
+    both = fq.fq_workspace_bytes([small, large], 2)
+    only_large = fq.fq_workspace_bytes([large], 2)
+    # alone: 15 partials + 5 * 3 slots; in the list: still 15 partials (one per slab) and the same slots,
+    # so the sizes add up except for the shared table
+    assert alone > 256 and both <= alone + only_large
+    # empty
+    i = fq.fq_layout(_desc(fq, outer=0, channels=4, inner=9))
+    assert (i.blocks, i.units_per_channel, i.wave_units) == (0, 0, 0)

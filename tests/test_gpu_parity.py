@@ -361,3 +361,26 @@ def test_randomised_shapes_alignments_and_flags():
                                     workloads.theta_for_scale(s), gy, **kw)
         _fwd_bwd(case, "random[%d]" % k, flags=flags, misalign=int(rng.integers(0, 8)),
                  want_q=(qmin >= -128 and qmax <= 127))
+
+
+@pytest.mark.parametrize("dtype, inner", [(np.float16, 1), (np.float16, 7), (np.float16, 147), (np.float16, 1001),
+                                          (np.float16, 2551), (np.float32, 5), (np.float32, 333),
+                                          (np.float32, 1275)])
+@pytest.mark.parametrize("flags, misalign", [(0, 0), (fq.FQ_FLAG_NO_DX, 1), (fq.FQ_FLAG_TWO_PASS, 0)])
+def test_wavefront_units_short_slabs(dtype, inner, flags, misalign):
+    """Thousands of short slabs: every wavefront owns a whole slab (fq_layout says so).  Odd slab
+    lengths put most slabs off the 16-byte grid (scalar heads and tails inside a wavefront), the
+    longest cases fill a wavefront's five rows; codes, y, gx and the scale gradients against the
+    oracle, in place as well."""
+    rng = np.random.default_rng(4000 + inner)
+    outer, c = 2, 2100
+    x = (rng.standard_normal((outer, c, inner)) * 2).astype(dtype)
+    gy = rng.standard_normal((outer, c, inner)).astype(dtype)
+    case = workloads.TensorCase("waves", (outer, c, inner), outer, c, inner, -128, 127, x,
+                                workloads.theta_for_scale(rng.uniform(0.01, 0.03, c)), gy)
+    probe = H.DeviceCase(case, want_q=False)
+    info = fq.fq_layout(probe.desc)
+    assert info.wave_units == 1 and info.units_per_channel == outer and info.blocks == (outer * c + 3) // 4
+    del probe
+    _fwd_bwd(case, "wave_units inner=%d/%s" % (inner, np.dtype(dtype).name), flags=flags, misalign=misalign,
+             inplace=(flags == 0))

@@ -54,39 +54,26 @@ def test_one_channel_many_blocks():
     _repeat(case, "stress/one_channel", 200)
 
 
-@pytest.mark.parametrize("dtype, outer, channels, inner", [
-    (np.float16, 32, 3, 19200),     # 2 blocks per slab: 64 per channel, the last count that shares one slot
-    (np.float16, 33, 3, 19200),     # 66 per channel: two-level tickets, first-level slots see 3 or 2 arrivals
-    (np.float32, 1, 1, 65 * 5120),  # one scale, well over a hundred blocks
-    (np.float32, 1, 1, 97 * 5120 + 13),   # ragged last block
-])
-def test_ticket_levels_around_the_threshold(dtype, outer, channels, inner):
-    rng = np.random.Generator(np.random.Philox(outer * 1000 + channels))
+def _protocol_case(dtype, outer, channels, inner, units, waves, extra, iters=3):
+    """Fused backward against the two-launch mode, bit for bit, and against the oracle, on a shape
+    whose layout (fq_layout) is asserted first so that the intended protocol is the one running.
+    Channel 0 has an all-zero upstream gradient (a sum of +0.0 travels as -0.0 in the exchanges)."""
+    rng = np.random.Generator(np.random.Philox(7000 + outer * 31 + channels))
     x = (rng.standard_normal((outer, channels, inner)) * 2).astype(dtype)
     gy = rng.standard_normal(x.shape).astype(dtype)
-    theta = workloads.theta_for_scale(rng.uniform(0.02, 0.05, channels))
-    case = workloads.TensorCase("lv", x.shape, outer, channels, inner, -128, 127, x, theta, gy)
-    _repeat(case, "stress/levels %dx%dx%d" % (outer, channels, inner), 20)
-
-
-@pytest.mark.parametrize("blocks_per_channel", [1, 2, 3, 4, 5, 8, 64, 66, 130])
-def test_every_combination_protocol_equals_the_two_launch_mode_bitwise(blocks_per_channel):
-    """One block per slab (8192 FP16 elements), so a channel has exactly `outer` blocks: direct
-    write, exchange, exchange tree, tickets, two-level tickets.  Each must give the bits of the
-    two-launch mode (and the oracle's values); channel 0 has an all-zero upstream gradient."""
-    outer, channels, inner = blocks_per_channel, 5, 8192
-    rng = np.random.Generator(np.random.Philox(7000 + outer))
-    x = (rng.standard_normal((outer, channels, inner)) * 2).astype(np.float16)
-    gy = rng.standard_normal(x.shape).astype(np.float16)
     gy[:, 0, :] = 0.0
     theta = workloads.theta_for_scale(rng.uniform(0.02, 0.05, channels))
     case = workloads.TensorCase("proto", x.shape, outer, channels, inner, -128, 127, x, theta, gy)
-    H.say("stress/protocols: %d blocks per channel" % outer)
     got = {}
     for flags in (0, fq.FQ_FLAG_TWO_PASS):
         dc = H.DeviceCase(case, want_q=False, flags=flags)
+        info = fq.fq_layout(dc.desc)
+        assert (info.units_per_channel, info.wave_units, info.extra_slots) == (units, waves, extra), (
+            info.units_per_channel, info.wave_units, info.extra_slots)
+        H.say("stress/protocols: %dx%dx%d %s: %d units per channel, wave units %d, extra slots %d, flags %d" % (
+            outer, channels, inner, np.dtype(dtype).name, units, waves, extra, flags))
         ws = H.workspace_for(dc.desc, fq.FQ_MODE_BACKWARD)
-        for rep in range(3):                       # the slots must be back at zero after every call
+        for rep in range(iters):                   # the slots must be back at zero after every call
             dc.gs.fill_(float("nan"))
             dc.gtheta.fill_(float("nan"))
             fq.fq_backward(dc.desc, ws)
@@ -94,7 +81,39 @@ def test_every_combination_protocol_equals_the_two_launch_mode_bitwise(blocks_pe
         if flags == 0:
             ref = H.oracle_forward(case)
             H.check_backward(dc, ref[0], ref[1], "stress/protocols")
-        got[flags] = (dc.host("gs"), dc.host("gtheta"))
+        got[flags] = (dc.host("gs"), dc.host("gtheta"), dc.host("gx"))
     for a, b in zip(got[0], got[fq.FQ_FLAG_TWO_PASS]):
-        assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (blocks_per_channel, a, b)
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), (units, a, b)
     assert got[0][0][0] == 0.0 and not np.signbit(got[0][0][0])
+
+
+@pytest.mark.parametrize("outer, extra", [(1, 0), (2, 0), (3, 2), (4, 2), (5, 0), (8, 0), (16, 0), (17, 16),
+                                          (40, 16), (66, 16), (130, 16), (256, 16), (257, 32), (300, 32)])
+def test_wavefront_units_every_protocol(outer, extra):
+    """Short slabs (40 FP16 elements) and thousands of them: one wavefront per slab, so a channel
+    has exactly `outer` units: direct write, exchange, exchange tree, tickets, two-level tickets."""
+    _protocol_case(np.float16, outer, 4100, 40, outer, 1, extra, iters=2)
+
+
+@pytest.mark.parametrize("dtype, outer, inner, units, extra", [
+    (np.float16, 1, 19200, 2, 0),        # the headline layout: exchange
+    (np.float16, 1, 28800, 3, 2),        # exchange tree, three blocks
+    (np.float16, 1, 22560, 4, 2),        # exchange tree, four blocks
+    (np.float32, 1, 9600 * 3, 6, 0),     # tickets on one slot
+    (np.float16, 8, 19200, 16, 0),       # the last count that shares one slot
+    (np.float16, 9, 19200, 18, 16),      # two-level tickets
+])
+def test_block_units_every_protocol(dtype, outer, inner, units, extra):
+    _protocol_case(dtype, outer, 384, inner, units, 0, extra, iters=2)
+
+
+def test_one_scale_many_blocks_two_level_tickets():
+    rng = np.random.Generator(np.random.Philox(77))
+    n = 97 * 5120 + 13                                              # ragged last block
+    x = (rng.standard_normal(n) * 2).astype(np.float32)
+    gy = rng.standard_normal(n).astype(np.float32)
+    case = workloads.TensorCase("one", (n,), 1, 1, n, -128, 127, x, workloads.theta_for_scale([0.03]), gy)
+    dc = H.DeviceCase(case, want_q=False)
+    info = fq.fq_layout(dc.desc)
+    assert info.units_per_channel > 16 and info.extra_slots in (16, 32) and info.wave_units == 0
+    _repeat(case, "stress/one_scale %d blocks" % info.units_per_channel, 20)
