@@ -367,7 +367,9 @@ def main():
                 kname = "forward_multi_kernel" if multi else "forward_kernel<%s>" % dt
             headline = args.workload == "feature_fp16_per_channel"
             traffic = None
-            if headline and train:
+            if args.cache_warm:
+                pass                                   # the counters were taken on the HBM-cold ring
+            elif headline and train:
                 traffic = TRAFFIC_BYTES_PER_LAUNCH
             elif headline and not codes:
                 traffic = FORWARD_TRAFFIC_BYTES_PER_LAUNCH
