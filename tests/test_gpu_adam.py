@@ -23,13 +23,26 @@ def _close(got, ref, what):
     return float(np.mean(got == ref))
 
 
+def _short_slab_case(outer):
+    """4200 channels of 96 FP16 elements each: one wavefront per slab, `outer` units per channel."""
+    rng = np.random.Generator(np.random.Philox(900 + outer))
+    c, inner = 4200, 96
+    x = (rng.standard_normal((outer, c, inner)) * 1.5).astype(np.float16)
+    gy = rng.standard_normal(x.shape).astype(np.float16)
+    theta = workloads.theta_for_scale(rng.uniform(0.02, 0.05, c))
+    return workloads.TensorCase("short", x.shape, outer, c, inner, -128, 127, x, theta, gy)
+
+
 @pytest.mark.parametrize("in_place", [True, False])
 @pytest.mark.parametrize("flags", [0, fq.FQ_FLAG_TWO_PASS])
-def test_adam_steps_single_tensor(in_place, flags):
-    case = workloads.train_batch_fp16(shape=(3, 10, 60, 80))[0]
-    H.say("adam single in_place=%s flags=%d" % (in_place, flags))
+@pytest.mark.parametrize("shape", ["blocks", "waves1", "waves2", "waves6"])
+def test_adam_steps_single_tensor(in_place, flags, shape):
+    case = (workloads.train_batch_fp16(shape=(3, 10, 60, 80))[0] if shape == "blocks"
+            else _short_slab_case(int(shape[5:])))
+    H.say("adam single %s in_place=%s flags=%d" % (shape, in_place, flags))
     c = case.channels
     dc = H.DeviceCase(case, want_q=False, flags=flags)
+    assert fq.fq_layout(dc.desc).wave_units == (0 if shape == "blocks" else 1)
     ws = H.workspace_for(dc.desc, fq.FQ_MODE_BACKWARD)
     m_d, v_d = torch.zeros(c, device="cuda"), torch.zeros(c, device="cuda")
     out_d = dc.theta if in_place else torch.full((c,), float("nan"), device="cuda")
