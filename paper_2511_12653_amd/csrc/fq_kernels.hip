@@ -6,7 +6,9 @@
 // [outer, channel] slab, so the scale is uniform over the block; lanes move 128-bit vectors
 // (global_load/store_dwordx4, non-temporal), FP16 is widened/narrowed in registers.  Backward adds
 // a DPP wavefront reduction, an LDS block reduction and a fixed-order combination of the blocks
-// of a channel (direct, by atomic exchange, or by ticket: see backward_block); no float atomics.
+// of a channel (direct, by atomic exchange, or by ticket: see combine); no float atomics.
+// Tensors whose slabs are short are cut per wavefront instead (one slab per wavefront, four to a
+// block, no barrier: forward_dispatch, backward_waves) when the launch has blocks to spare.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
