@@ -138,3 +138,39 @@ def test_full_size_list_about_1GiB():
     total = sum(c.x.nbytes for c in cases)
     assert len(cases) == 64 and abs(total - 2 ** 30) <= 0.05 * 2 ** 30
     _run_list(cases, "multi/full", want_q=False)
+
+
+@pytest.mark.timeout(300)
+def test_list_mixing_block_and_wavefront_units_with_codes():
+    """A list with enough blocks that its short-slab members are cut per wavefront (checked with
+    fq_workspace_bytes: one partial sum per slab), next to ordinary members, int8 codes wanted for
+    all: forward with codes, backward, against the oracle and against the single-tensor calls."""
+    rng = np.random.Generator(np.random.Philox(5150))
+    big = workloads.train_batch_fp16(shape=(4, 96, 120, 160))[0]            # 768 blocks
+
+    def short(outer, c, inner, dtype):
+        x = (rng.standard_normal((outer, c, inner)) * 2).astype(dtype)
+        gy = rng.standard_normal(x.shape).astype(dtype)
+        return workloads.TensorCase("short", x.shape, outer, c, inner, -128, 127, x,
+                                    workloads.theta_for_scale(rng.uniform(0.01, 0.03, c)), gy)
+
+    cases = [short(2, 1500, 147, np.float16), big, short(1, 900, 333, np.float32), short(5, 300, 8, np.float16)]
+    dcs, ws = _run_list(cases, "multi/mixed_units", want_q=True)
+    descs = [d.desc for d in dcs]
+    # 3000 + 900 + 1500 slabs in block units would be 5400 blocks on top of 768: the launch has blocks
+    # to spare, so those members need one partial per slab but only a quarter of the blocks
+    alone = [fq.fq_layout(d) for d in descs]
+    assert [a.wave_units for a in alone] == [0, 0, 0, 0]                   # each on its own: too small
+    total = fq.fq_workspace_bytes(descs, fq.FQ_MODE_BACKWARD)
+    separately = sum(fq.fq_workspace_bytes([d], fq.FQ_MODE_BACKWARD) for d in descs)
+    assert total <= separately
+    H.say("multi/mixed_units: single-tensor calls")
+    for c, d in zip(cases, dcs):
+        one = H.DeviceCase(c, want_q=True)
+        fq.fq_forward(one.desc)
+        ws1 = H.workspace_for(one.desc, fq.FQ_MODE_BACKWARD)
+        fq.fq_backward(one.desc, ws1)
+        torch.cuda.synchronize()
+        for name in ("y", "q", "gx", "gs", "gtheta", "s"):
+            a, b = getattr(one, name), getattr(d, name)
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), name
