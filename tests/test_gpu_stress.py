@@ -1,7 +1,11 @@
-"""Repeat the backward pass many times on the same inputs and workspace: the cross-block
-combination (atomic exchange for two blocks per channel, tickets for more) must hand every
-channel's finisher the other blocks' sums of THIS launch -- a stale or missing sum would change
-bits.  Outputs are poisoned before every launch and compared on the device."""
+"""Repeat the backward pass many times on one workspace: the cross-block combination (atomic
+exchange for two blocks per channel, tickets for more) must hand every channel's finisher the
+other blocks' sums of THIS launch.  Two cases of the same shape but different upstream gradients
+take turns on the workspace, so a partial sum left over from the launch before belongs to the
+other case and would change bits; outputs are poisoned before every launch and compared on the
+device."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -14,25 +18,40 @@ import _gpu_harness as H
 pytestmark = pytest.mark.gpu
 
 
+def _other_gradient(case):
+    """The same tensor with another upstream gradient (every partial sum differs)."""
+    rng = np.random.Generator(np.random.Philox(991))
+    gy = (case.gy.astype(np.float32) * -0.75 + rng.standard_normal(case.gy.shape).astype(np.float32)).astype(
+        case.gy.dtype)
+    return dataclasses.replace(case, gy=gy)
+
+
 def _repeat(case, label, iters):
-    H.say("%s: %d launches" % (label, iters))
-    dc = H.DeviceCase(case, want_q=False)
-    ws = H.workspace_for(dc.desc, fq.FQ_MODE_BACKWARD)
-    fq.fq_backward(dc.desc, ws)
-    torch.cuda.synchronize()
-    ref = H.oracle_forward(case)
-    H.check_backward(dc, ref[0], ref[1], label)
-    want = [t.clone() for t in (dc.gs, dc.gtheta, dc.gx)]
+    H.say("%s: %d launches, two gradients alternating on one workspace" % (label, iters))
+    cases = (case, _other_gradient(case))
+    dcs = [H.DeviceCase(c, want_q=False) for c in cases]
+    ws = H.workspace_for(dcs[0].desc, fq.FQ_MODE_BACKWARD)
+    assert fq.fq_workspace_bytes(dcs[1].desc, fq.FQ_MODE_BACKWARD) == ws.numel() * 4
+    want = []
+    for c, dc in zip(cases, dcs):
+        fq.fq_backward(dc.desc, ws)
+        torch.cuda.synchronize()
+        ref = H.oracle_forward(c)
+        H.check_backward(dc, ref[0], ref[1], label)
+        want.append([t.clone() for t in (dc.gs, dc.gtheta, dc.gx)])
+    assert not torch.equal(want[0][0], want[1][0]), label + ": the two cases must differ"
     bad = torch.zeros((), dtype=torch.int64, device="cuda")
-    for _ in range(iters):
+    for i in range(iters):
+        dc, w = dcs[i % 2], want[i % 2]
         dc.gs.fill_(float("nan"))
         dc.gtheta.fill_(float("nan"))
         fq.fq_backward(dc.desc, ws)
-        for got, w in zip((dc.gs, dc.gtheta), want[:2]):
-            bad += (got.view(torch.int32) != w.view(torch.int32)).sum()
+        for got, ww in zip((dc.gs, dc.gtheta), w[:2]):
+            bad += (got.view(torch.int32) != ww.view(torch.int32)).sum()
     torch.cuda.synchronize()
     assert int(bad.item()) == 0, "%s: %d mismatching words over %d launches" % (label, int(bad.item()), iters)
-    assert torch.equal(dc.gx.view(torch.uint8), want[2].view(torch.uint8))
+    for dc, w in zip(dcs, want):
+        assert torch.equal(dc.gx.view(torch.uint8), w[2].view(torch.uint8))
 
 
 def test_two_blocks_per_channel_exchange():
