@@ -160,6 +160,27 @@ fq_status fq_forward(const fq_tensor *t, void *hip_stream);
 fq_status fq_backward(const fq_tensor *t, void *workspace, size_t ws_bytes, void *hip_stream);
 
 /*
+ * fq_backward for callers that cannot allocate device memory or may not have anyone allocate on
+ * their behalf: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same inputs, outputs, flags and results (bit for bit) as fq_backward, but the
+ * partial sums and slots live in a scratch array built into the library instead of a caller's
+ * workspace: FQ_STATIC_SCRATCH_BYTES of device memory per GPU, held from the moment the library's
+ * code is loaded on that GPU until the process ends.  The call itself allocates and frees
+ * nothing, on the device or on the host, and does not synchronise.  Limits: at most
+ * FQ_STATIC_MAX_UNITS partial sums (fq_layout: units_per_channel * channels) and
+ * FQ_STATIC_MAX_SLOTS slots (channels * (1 + extra_slots)); a larger tensor is refused with
+ * FQ_ERR_WORKSPACE before anything is enqueued.  The first call on a GPU looks the array's device
+ * address up and zeroes its slots with a small fill kernel on `hip_stream`; make that call
+ * outside any graph capture.  All calls on one GPU share that GPU's array: two calls that can
+ * overlap in time (different streams, or graphs replayed concurrently) race; calls ordered on one
+ * stream do not.
+ */
+#define FQ_STATIC_SCRATCH_BYTES (1u << 20)
+#define FQ_STATIC_MAX_SLOTS 32768
+#define FQ_STATIC_MAX_UNITS 98304
+fq_status fq_backward_static(const fq_tensor *t, void *hip_stream);
+
+/*
  * The same forward (mode FQ_MODE_FORWARD) or backward (FQ_MODE_BACKWARD) for a whole list
  * of tensors -- e.g. the activations and weights of all 22 quantized convolutions of the
  * front end (Sec. 4.3.4 "Quantization coverage") -- in ONE kernel launch instead of one to three per layer

@@ -155,6 +155,8 @@ _lib.fq_forward.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_void_p]
 _lib.fq_forward.restype = ctypes.c_int
 _lib.fq_backward.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fq_backward.restype = ctypes.c_int
+_lib.fq_backward_static.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_void_p]
+_lib.fq_backward_static.restype = ctypes.c_int
 _lib.fq_multi_tensor.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_int, ctypes.c_int,
                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fq_multi_tensor.restype = ctypes.c_int
@@ -246,6 +248,10 @@ def fq_forward(t: FqTensor, stream=None):
 def fq_backward(t: FqTensor, workspace, stream=None):
     p, nbytes = _ws(workspace)
     _check(_lib.fq_backward(ctypes.byref(t), p, nbytes, _stream(stream)))
+
+
+def fq_backward_static(t: FqTensor, stream=None):
+    _check(_lib.fq_backward_static(ctypes.byref(t), _stream(stream)))
 
 
 def fq_multi_tensor(tensors, mode, workspace, stream=None):

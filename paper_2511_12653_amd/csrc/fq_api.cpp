@@ -12,6 +12,10 @@
 #include "../../include/fq.h"
 #include "fq_internal.h"
 
+static_assert(FQ_STATIC_SCRATCH_BYTES == fq::kStaticScratchBytes && FQ_STATIC_MAX_SLOTS * 8 == fq::kStaticSlotBytes &&
+                  FQ_STATIC_MAX_UNITS * 8 == fq::kStaticPartialBytes,
+              "the limits stated in fq.h are the ones the library is built with");
+
 namespace fq {
 namespace {
 
@@ -219,50 +223,67 @@ fq_status make_layout(const fq_tensor *ts, int n, int mode, Layout &L)
     return FQ_OK;
 }
 
+// Where a tensor's share of a launch begins: grid block, finalize-grid channel, 64-bit slot and
+// partial sum.
+struct Cursor {
+    long long block = 0, chan = 0, slot = 0, unit = 0;
+};
+
+// Device descriptor of one tensor; `partials` / `slots` are the launch's arrays of partial sums and
+// of 64-bit slots (nullptr: forward, nothing is reduced).
+DevTensor describe(const fq_tensor &t, const Plan &p, int mode, double *partials, unsigned long long *slots,
+                   const Cursor &at)
+{
+    DevTensor d;
+    std::memset(&d, 0, sizeof d);
+    d.x = t.x; d.y = t.y; d.q = t.q; d.theta = t.theta; d.s = t.s;
+    d.gy = t.gy; d.gx = t.gx; d.gs = t.gs; d.gtheta = t.gtheta;
+    d.partial = partials ? partials + at.unit : nullptr;
+    d.slot = slots ? slots + at.slot : nullptr;
+    d.inner = t.inner;
+    d.slabs = p.slabs;
+    d.channels = (unsigned)t.channels;
+    d.outer = p.numel ? (unsigned)t.outer : 0u;
+    d.cps = p.cps;
+    d.chunk = p.chunk;
+    d.block_begin = (unsigned)at.block;
+    d.chan_begin = (unsigned)at.chan;
+    d.sub = p.sub;
+    d.wave_units = p.waves ? 1u : 0u;
+    d.dtype = t.dtype;
+    d.lo = (float)t.qmin;
+    d.hi = (float)t.qmax;
+    d.eps = t.eps; d.s_min = t.s_min; d.s_max = t.s_max;
+    d.flags = t.flags;
+    if (mode == FQ_MODE_BACKWARD && t.adam && t.channels > 0) {   // validated for this mode only
+        const fq_adam &a = *t.adam;
+        d.adam_m = a.m; d.adam_v = a.v; d.adam_theta_out = a.theta_out;
+        d.adam_lr = (float)a.lr;
+        d.adam_beta1 = (float)a.beta1; d.adam_one_minus_beta1 = (float)(1.0 - a.beta1);
+        d.adam_beta2 = (float)a.beta2; d.adam_one_minus_beta2 = (float)(1.0 - a.beta2);
+        d.adam_eps = (float)a.eps;
+        d.adam_bc1 = (float)(1.0 - std::pow(a.beta1, (double)a.step));
+        d.adam_bc2 = (float)(1.0 - std::pow(a.beta2, (double)a.step));
+    }
+    return d;
+}
+
 // Fill the device descriptors; partial/counter pointers are carved out of the workspace.
 void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *workspace,
                  std::vector<DevTensor> &out)
 {
     out.resize((size_t)n);
-    long long block = 0, chan = 0, slot = 0, unit = 0;
+    double *partials = workspace ? (double *)(workspace + L.partial_off) : nullptr;
+    unsigned long long *slots = workspace ? (unsigned long long *)(workspace + L.counter_off) : nullptr;
+    Cursor at;
     for (int i = 0; i < n; ++i) {
         const fq_tensor &t = ts[i];
         const Plan &p = L.plans[(size_t)i];
-        DevTensor &d = out[(size_t)i];
-        std::memset(&d, 0, sizeof d);
-        d.x = t.x; d.y = t.y; d.q = t.q; d.theta = t.theta; d.s = t.s;
-        d.gy = t.gy; d.gx = t.gx; d.gs = t.gs; d.gtheta = t.gtheta;
-        d.partial = workspace ? (double *)(workspace + L.partial_off) + unit : nullptr;
-        d.slot = workspace ? (unsigned long long *)(workspace + L.counter_off) + slot : nullptr;
-        d.inner = t.inner;
-        d.slabs = p.slabs;
-        d.channels = (unsigned)t.channels;
-        d.outer = p.numel ? (unsigned)t.outer : 0u;
-        d.cps = p.cps;
-        d.chunk = p.chunk;
-        d.block_begin = (unsigned)block;
-        d.chan_begin = (unsigned)chan;
-        d.sub = p.sub;
-        d.wave_units = p.waves ? 1u : 0u;
-        d.dtype = t.dtype;
-        d.lo = (float)t.qmin;
-        d.hi = (float)t.qmax;
-        d.eps = t.eps; d.s_min = t.s_min; d.s_max = t.s_max;
-        d.flags = t.flags;
-        if (mode == FQ_MODE_BACKWARD && t.adam && t.channels > 0) {   // validated for this mode only
-            const fq_adam &a = *t.adam;
-            d.adam_m = a.m; d.adam_v = a.v; d.adam_theta_out = a.theta_out;
-            d.adam_lr = (float)a.lr;
-            d.adam_beta1 = (float)a.beta1; d.adam_one_minus_beta1 = (float)(1.0 - a.beta1);
-            d.adam_beta2 = (float)a.beta2; d.adam_one_minus_beta2 = (float)(1.0 - a.beta2);
-            d.adam_eps = (float)a.eps;
-            d.adam_bc1 = (float)(1.0 - std::pow(a.beta1, (double)a.step));
-            d.adam_bc2 = (float)(1.0 - std::pow(a.beta2, (double)a.step));
-        }
-        block += p.blocks;
-        unit += p.units;
-        chan += t.channels;
-        slot += t.channels * (1 + (long long)p.sub);
+        out[(size_t)i] = describe(t, p, mode, partials, slots, at);
+        at.block += p.blocks;
+        at.unit += p.units;
+        at.chan += t.channels;
+        at.slot += t.channels * (1 + (long long)p.sub);
     }
 }
 
@@ -392,6 +413,43 @@ fq_status run(const fq_tensor *ts, int n, int mode, bool use_table, void *worksp
     return launch_prepared(P, stream);
 }
 
+// Plan of one tensor launched on its own, without any heap use: validation, the cut into units, and
+// the switch to one wavefront per slab for short slabs in a launch with blocks to spare.
+fq_status plan_single(const fq_tensor &t, int mode, Plan &p)
+{
+    fq_status st = validate_one(t, mode, p);
+    if (st != FQ_OK) return st;
+    if (p.blocks > kMaxBlocks || t.channels * (1 + (long long)p.sub) > 64 * kMaxBlocks) return FQ_ERR_SHAPE;
+    if (p.short_slabs && p.numel > 0 && p.blocks >= kWaveUnitsMinBlocks) (void)plan_tensor(t, p, true);
+    return FQ_OK;
+}
+
+// fq_backward with the partial sums and slots in the library's built-in scratch array.  Touches
+// no allocator, host or device: one descriptor on the stack, passed by value to the kernel.
+fq_status run_static(const fq_tensor &t, void *stream)
+{
+    Plan p;
+    fq_status st = plan_single(t, FQ_MODE_BACKWARD, p);
+    if (st != FQ_OK) return st;
+    const long long slots = t.channels * (1 + (long long)p.sub);
+    if ((unsigned long long)slots * sizeof(unsigned long long) > kStaticSlotBytes ||
+        (unsigned long long)p.units * sizeof(double) > kStaticPartialBytes)
+        return FQ_ERR_WORKSPACE;
+    void *base = nullptr;
+    if (static_scratch(&base, stream) != 0) return FQ_ERR_LAUNCH;
+    Prepared P;                               // its table (a vector) stays empty: nothing is allocated
+    std::memset(&P.args, 0, sizeof P.args);
+    P.args.n = 1;
+    P.args.one = describe(t, p, FQ_MODE_BACKWARD, (double *)((char *)base + kStaticSlotBytes),
+                          (unsigned long long *)base, Cursor());
+    P.mode = FQ_MODE_BACKWARD;
+    P.blocks = p.blocks;
+    P.channels = t.channels;
+    P.any_empty_with_channels = p.numel == 0 && t.channels > 0;
+    P.two_pass = (t.flags & FQ_FLAG_TWO_PASS) != 0 || P.any_empty_with_channels;
+    return launch_prepared(P, stream);
+}
+
 }  // namespace
 
 int copy_table_async(void *dst_device, const void *src_host, size_t bytes, void *stream)
@@ -464,6 +522,12 @@ fq_status fq_backward(const fq_tensor *t, void *workspace, size_t ws_bytes, void
 {
     if (!t) return FQ_ERR_NULL;
     FQ_GUARDED(fq::run(t, 1, FQ_MODE_BACKWARD, false, workspace, ws_bytes, hip_stream), FQ_ERR_LAUNCH)
+}
+
+fq_status fq_backward_static(const fq_tensor *t, void *hip_stream)
+{
+    if (!t) return FQ_ERR_NULL;
+    FQ_GUARDED(fq::run_static(*t, hip_stream), FQ_ERR_LAUNCH)
 }
 
 fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode, void *workspace, size_t ws_bytes,

@@ -20,6 +20,11 @@ constexpr unsigned kTicketManyUnits = 256;     // beyond this many units per cha
 constexpr unsigned kTicketManySubSlots = 32;   // ... this many first-level slots
 constexpr unsigned kTreeBlocks = 4;      // up to this many blocks per channel combine by atomic exchange alone
 
+// Scratch memory built into the library for fq_backward_static: [slots][partial sums].
+constexpr size_t kStaticScratchBytes = 1u << 20;                 // per GPU
+constexpr size_t kStaticSlotBytes = 256u << 10;                  // 32768 64-bit slots
+constexpr size_t kStaticPartialBytes = kStaticScratchBytes - kStaticSlotBytes;   // 98304 partial sums
+
 // Device-side view of one tensor.  Built on the host; passed as a kernel argument for
 // single-tensor calls, or as an array in device memory for the multi-tensor launch.
 struct DevTensor {
@@ -70,5 +75,6 @@ int launch_finalize(const KArgs &a, unsigned total_channels, void *stream);
 int launch_scale_only(const KArgs &a, unsigned total_channels, void *stream);
 int launch_fill_zero(void *p, size_t bytes, void *stream);
 int copy_table_async(void *dst_device, const void *src_host, size_t bytes, void *stream);
+int static_scratch(void **ptr, void *stream);
 
 }  // namespace fq

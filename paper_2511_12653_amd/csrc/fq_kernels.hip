@@ -12,6 +12,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "fq_device.h"
 #include "fq_internal.h"
 
@@ -867,6 +869,44 @@ __global__ void __launch_bounds__(kBlock) fill_zero_kernel(unsigned *p, size_t w
 }
 
 }  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// Built-in scratch memory for callers that cannot allocate (fq_backward_static).  One array per
+// GPU, held from the moment the code object is loaded until the process ends.  In host code the
+// array's name stands for the symbol, not for a device address: the address on the current
+// device comes from hipGetSymbolAddress, once per device, and only that pointer is ever handed
+// to kernels.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices];     // per device; nullptr until the first call on that device
+}  // namespace
+
+// Device address of the scratch array on the current device (0 = success, else a hipError_t).
+// The first call on a device also zeroes the slot region with a fill kernel on `stream`; the
+// loader has zeroed it already and every completed backward leaves it zero, this only makes the
+// starting state explicit.
+int static_scratch(void **ptr, void *stream)
+{
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return (int)e;
+    if (device < 0 || device >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[device]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        const int rc = launch_fill_zero(p, kStaticSlotBytes, stream);
+        if (rc != 0) return rc;
+        scratch_ptr[device] = p;
+    }
+    *ptr = scratch_ptr[device];
+    return 0;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Launchers.

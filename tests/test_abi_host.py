@@ -241,3 +241,25 @@ def test_layout_info(fq):
     # empty
     i = fq.fq_layout(_desc(fq, outer=0, channels=4, inner=9))
     assert (i.blocks, i.units_per_channel, i.wave_units) == (0, 0, 0)
+
+
+def test_static_backward_refuses_what_its_scratch_cannot_hold(fq):
+    """fq_backward_static validates and sizes on the host before it touches the GPU: descriptors
+    that do not validate give their own code, tensors with more partial sums or slots than the
+    built-in scratch array holds give FQ_ERR_WORKSPACE."""
+    lib = ctypes.CDLL(fq.library_path())
+    lib.fq_backward_static.argtypes = [ctypes.POINTER(fq.FqTensor), ctypes.c_void_p]
+    lib.fq_backward_static.restype = ctypes.c_int
+    call = lambda d: lib.fq_backward_static(ctypes.byref(d), None)
+    assert lib.fq_backward_static(None, None) == -1
+    assert call(_desc(fq, gy=None)) == -1
+    assert call(_desc(fq, qmin=5)) == -4
+    # one scale over 98305 chunks of 10240 FP16 elements: one partial sum too many
+    big = _desc(fq, outer=1, channels=1, inner=98305 * 10240, x=1 << 40, gy=2 << 40, gx=3 << 40)
+    info = fq.fq_layout(big)
+    assert info.units_per_channel == 98305
+    assert call(big) == -6
+    # 40000 channels of one short slab each: more slots than the scratch array has
+    assert call(_desc(fq, outer=1, channels=40000, inner=8, x=1 << 40, gy=2 << 40, gx=3 << 40)) == -6
+    hdr = open(os.path.join(ROOT, "include", "fq.h")).read()
+    assert "#define FQ_STATIC_MAX_UNITS 98304" in hdr and "#define FQ_STATIC_MAX_SLOTS 32768" in hdr
