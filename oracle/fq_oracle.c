@@ -32,6 +32,17 @@
 
 enum { FQO_F16 = 0, FQO_F32 = 1 };
 
+/*
+ * Threads for fqo_forward / fqo_backward (default 1).  The work is split over channels only:
+ * every element is computed exactly as with one thread, and every channel's sum is still formed
+ * by one thread, sequentially, in the same element order, so the results do not depend on the
+ * count.  Used by the benchmark's all-cores baseline; the tests run with one thread and check
+ * once that more threads change nothing.
+ */
+static int fqo_threads = 1;
+void fqo_set_threads(int n) { fqo_threads = n < 1 ? 1 : n; }
+int fqo_get_threads(void) { return fqo_threads; }
+
 /* ---- binary16 <-> binary32, written out from the IEEE-754 formats ------- */
 
 /* Widen a binary16 bit pattern; every binary16 value is exact in binary32. */
@@ -165,8 +176,9 @@ void fqo_forward(const void *x, int dtype, int64_t outer, int64_t C, int64_t inn
                  const float *s, int32_t qmin, int32_t qmax, void *y, int32_t *q)
 {
     const float lo = (float)qmin, hi = (float)qmax;
-    for (int64_t o = 0; o < outer; ++o)
-        for (int64_t c = 0; c < C; ++c)
+#pragma omp parallel for schedule(static) num_threads(fqo_threads) if (fqo_threads > 1)
+    for (int64_t c = 0; c < C; ++c)
+        for (int64_t o = 0; o < outer; ++o)
             for (int64_t k = 0; k < inner; ++k) {
                 int64_t i = (o * C + c) * inner + k;
                 float xf = load_elem(x, dtype, i);
@@ -199,12 +211,11 @@ void fqo_backward(const void *x, const void *gy, int dtype,
                   void *gx, double *acc, double *aabs, float *gs, float *gtheta)
 {
     const float lo = (float)qmin, hi = (float)qmax;
+    /* channel by channel; within a channel the terms are added in memory order (o, then k) */
+#pragma omp parallel for schedule(static) num_threads(fqo_threads) if (fqo_threads > 1)
     for (int64_t c = 0; c < C; ++c) {
-        acc[c] = 0.0;
-        if (aabs) aabs[c] = 0.0;
-    }
-    for (int64_t o = 0; o < outer; ++o)
-        for (int64_t c = 0; c < C; ++c)
+        double sum = 0.0, sum_abs = 0.0;
+        for (int64_t o = 0; o < outer; ++o)
             for (int64_t k = 0; k < inner; ++k) {
                 int64_t i = (o * C + c) * inner + k;
                 float xf = load_elem(x, dtype, i);
@@ -232,9 +243,12 @@ void fqo_backward(const void *x, const void *gy, int dtype,
                     }
                 }
                 double term = (double)g * (double)t;
-                acc[c] += term;
-                if (aabs) aabs[c] += fabs(term);
+                sum += term;
+                sum_abs += fabs(term);
             }
+        acc[c] = sum;
+        if (aabs) aabs[c] = sum_abs;
+    }
     for (int64_t c = 0; c < C; ++c) {
         if (gs) gs[c] = (float)acc[c];
         if (gtheta) {

@@ -43,6 +43,10 @@ def lib():
         L.fqo_distill.restype = None
         L.fqo_adam.argtypes = [vp, i64, f32, f32, f32, f32, f32, f32, f32, f32, vp, vp, vp, vp]
         L.fqo_adam.restype = None
+        L.fqo_set_threads.argtypes = [ctypes.c_int]
+        L.fqo_set_threads.restype = None
+        L.fqo_get_threads.argtypes = []
+        L.fqo_get_threads.restype = ctypes.c_int
         _LIB = L
     return _LIB
 
@@ -60,6 +64,13 @@ def float_to_half(value) -> int:
 
 
 FLT_MIN = float(np.finfo(np.float32).tiny)
+
+
+def set_threads(n: int) -> int:
+    """Threads for forward / backward (channels are split over them; results do not change).
+    Returns the count now in force."""
+    lib().fqo_set_threads(int(n))
+    return int(lib().fqo_get_threads())
 
 
 def scale(theta, eps=0.0, s_min=FLT_MIN, s_max=float("inf")):

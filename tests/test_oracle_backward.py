@@ -165,3 +165,27 @@ def test_scale_clamp_gates_theta_gradient(oracle):
     assert r["gtheta"][0] == 0 and r["gtheta"][2] == 0
     assert r["gtheta"][1] == np.float32(r["acc"][1] * 0.5)       # sigmoid(0) = 1/2
     assert np.all(r["gs"] == r["acc"].astype(np.float32))
+
+
+def test_threads_change_nothing(oracle):
+    """The benchmark's all-cores baseline splits channels over threads: every output must have the
+    same bits as with one thread (each channel's sum is still one thread's sequential sum)."""
+    rng = np.random.Generator(np.random.Philox(4242))
+    outer, channels, inner = 3, 37, 501
+    for dtype in (np.float16, np.float32):
+        x = (rng.standard_normal((outer, channels, inner)) * 3).astype(dtype)
+        gy = rng.standard_normal(x.shape).astype(dtype)
+        theta = rng.uniform(-4, -2, channels).astype(np.float32)
+        s, active = oracle.scale(theta)
+        ref = None
+        for threads in (1, 4, 7):
+            assert oracle.set_threads(threads) == threads
+            y, q = oracle.forward(x, s, -128, 127, outer, channels, inner)
+            r = oracle.backward(x, gy, s, theta, active, -128, 127, outer, channels, inner)
+            got = [y.view(np.uint8), q, r["gx"].view(np.uint8), r["acc"].view(np.uint64), r["aabs"].view(np.uint64),
+                   r["gs"].view(np.uint32), r["gtheta"].view(np.uint32)]
+            if ref is None:
+                ref = got
+            for a, b in zip(ref, got):
+                assert np.array_equal(a, b)
+        oracle.set_threads(1)
