@@ -250,6 +250,19 @@ typedef struct fq_distill {
 size_t fq_distill_workspace_bytes(const fq_distill *d);   /* 0 if d does not validate; host only */
 fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes, void *hip_stream);
 
+/*
+ * Measurement aid, not part of the operation: a streaming kernel without arithmetic in the launch
+ * shape of fq_forward / fq_backward (256-thread blocks, 20 KiB of each stream per block, every
+ * load issued before the first store, non-temporal), so that a benchmark can put what the memory
+ * system and the launch alone take for the same bytes beside the library's own figures.
+ *   inputs = 0: the launch alone (blocks that return at once; the pointers are not touched)
+ *   inputs = 1: out = a             (the forward's traffic: `bytes` read, `bytes` written)
+ *   inputs = 2: out = a XOR b       (the backward's traffic: 2 x `bytes` read, `bytes` written)
+ * a, b, out: device pointers, 16-byte aligned, `bytes` (a multiple of 16) each; out may not
+ * overlap a or b partially.
+ */
+fq_status fq_probe_stream(int inputs, const void *a, const void *b, void *out, size_t bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *fq_status_string(fq_status status);
 

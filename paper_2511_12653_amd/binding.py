@@ -157,6 +157,9 @@ _lib.fq_backward.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_void_p, ctypes.c
 _lib.fq_backward.restype = ctypes.c_int
 _lib.fq_backward_static.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_void_p]
 _lib.fq_backward_static.restype = ctypes.c_int
+_lib.fq_probe_stream.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                 ctypes.c_void_p]
+_lib.fq_probe_stream.restype = ctypes.c_int
 _lib.fq_multi_tensor.argtypes = [ctypes.POINTER(FqTensor), ctypes.c_int, ctypes.c_int,
                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fq_multi_tensor.restype = ctypes.c_int
@@ -288,6 +291,17 @@ def fq_distill_workspace_bytes(d: FqDistill) -> int:
 def fq_distill_loss(d: FqDistill, workspace, stream=None):
     p, nbytes = _ws(workspace)
     _check(_lib.fq_distill_loss(ctypes.byref(d), p, nbytes, _stream(stream)))
+
+
+def fq_probe_stream(inputs, a, b, out, nbytes, stream=None):
+    """a, b, out: torch tensors (or None where unused); see include/fq.h."""
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(_lib.fq_probe_stream(int(inputs), ptr(a), ptr(b), ptr(out), int(nbytes), _stream(stream)))
+
+
+def fq_probe_stream_raw(inputs, a_ptr, b_ptr, out_ptr, nbytes, stream_ptr):
+    """The same with raw device addresses and a raw stream handle (0 = none / default stream)."""
+    _check(_lib.fq_probe_stream(inputs, a_ptr or None, b_ptr or None, out_ptr or None, nbytes, stream_ptr or None))
 
 
 def fq_layout(t: FqTensor) -> FqLayoutInfo:

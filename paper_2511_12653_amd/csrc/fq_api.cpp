@@ -268,6 +268,14 @@ DevTensor describe(const fq_tensor &t, const Plan &p, int mode, double *partials
     return d;
 }
 
+// A tensor launched on its own gets a three-dimensional grid (chunks per slab, channels, outer)
+// unless its slabs go one to a wavefront or an extent exceeds the grid's y/z limit.
+void set_grid_shape(DevTensor &d)
+{
+    d.grid3 = (!d.wave_units && d.cps > 0 && d.channels > 0 && d.outer > 0 && d.channels <= 65535u &&
+               d.outer <= 65535u) ? 1u : 0u;
+}
+
 // Fill the device descriptors; partial/counter pointers are carved out of the workspace.
 void build_table(const fq_tensor *ts, int n, int mode, const Layout &L, char *workspace,
                  std::vector<DevTensor> &out)
@@ -378,6 +386,7 @@ fq_status prepare(const fq_tensor *ts, int n, int mode, bool use_table, void *wo
             return FQ_ERR_LAUNCH;
     } else {
         P.args.one = table[0];
+        set_grid_shape(P.args.one);
     }
     P.blocks = L.blocks;
     P.channels = L.channels;
@@ -442,6 +451,7 @@ fq_status run_static(const fq_tensor &t, void *stream)
     P.args.n = 1;
     P.args.one = describe(t, p, FQ_MODE_BACKWARD, (double *)((char *)base + kStaticSlotBytes),
                           (unsigned long long *)base, Cursor());
+    set_grid_shape(P.args.one);
     P.mode = FQ_MODE_BACKWARD;
     P.blocks = p.blocks;
     P.channels = t.channels;
@@ -534,6 +544,16 @@ fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode, void *workspace,
                           void *hip_stream)
 {
     FQ_GUARDED(fq::run(ts, n, mode, true, workspace, ws_bytes, hip_stream), FQ_ERR_LAUNCH)
+}
+
+fq_status fq_probe_stream(int inputs, const void *a, const void *b, void *out, size_t bytes, void *hip_stream)
+{
+    if (inputs < 0 || inputs > 2 || bytes % fq::kVecBytes != 0 || bytes / fq::kVecBytes / fq::kChunkVecs > 0x7ffffffeull)
+        return FQ_ERR_SHAPE;
+    if (inputs >= 1 && bytes > 0 && (!a || !out || (inputs == 2 && !b))) return FQ_ERR_NULL;
+    if (!fq::aligned(a, fq::kVecBytes) || !fq::aligned(b, fq::kVecBytes) || !fq::aligned(out, fq::kVecBytes))
+        return FQ_ERR_ALIGN;
+    return fq::launch_probe(inputs, a, b, out, bytes, hip_stream) == 0 ? FQ_OK : FQ_ERR_LAUNCH;
 }
 
 struct fq_plan {

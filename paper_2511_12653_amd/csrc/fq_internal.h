@@ -11,6 +11,9 @@ constexpr int kVecBytes = 16;        // one 128-bit global load/store per lane
 constexpr int kChunkVecs = 1280;     // at most this many 128-bit vectors per block (20 KiB)
 constexpr int kWaveChunkVecs = kChunkVecs / (kBlock / 64);   // what one wavefront covers: 320 vectors
 constexpr int kComputeUnits = 256;   // MI355X; used by the host to balance blocks over the chip
+// A single-tensor backward launch of at most this many blocks has all of them resident at once
+// (three per compute unit) and takes the schedule made for one burst (backward_chunk, SHORT).
+constexpr unsigned kShortLaunchBlocks = 3 * kComputeUnits;
 // Units of a channel beyond kTicketFanIn draw their arrival tickets in two levels: that many
 // atomics on one address queue up at the memory-side atomic unit (60 units on one slot cost a
 // short-slab backward 17.4 us against 13.1 us with 16 first-level slots).
@@ -50,6 +53,7 @@ struct DevTensor {
     unsigned chan_begin;       // first channel of this tensor in the finalize grid
     unsigned wave_units;       // 1: slabs are short, every wavefront owns one (cps = 1, chunk = the slab);
                                // the tensor's blocks then number ceil(slabs / 4) and partial[] is per slab
+    unsigned grid3;            // 1: launched alone with a grid of (cps, channels, outer) blocks (see own_chunk)
     unsigned sub;              // extra slots per channel after the [channels] main ones: 0, 2 (pair slots of
                                // the exchange tree, 3 or 4 blocks per channel) or kTicketSubSlots
     int dtype;                 // 0 = FP16, 1 = FP32
@@ -76,5 +80,6 @@ int launch_scale_only(const KArgs &a, unsigned total_channels, void *stream);
 int launch_fill_zero(void *p, size_t bytes, void *stream);
 int copy_table_async(void *dst_device, const void *src_host, size_t bytes, void *stream);
 int static_scratch(void **ptr, void *stream);
+int launch_probe(int inputs, const void *a, const void *b, void *out, size_t bytes, void *stream);
 
 }  // namespace fq

@@ -206,6 +206,11 @@ __device__ __forceinline__ void wait_stores_acknowledged() { asm volatile("s_wai
 // through it: measured 41 -> 45 us on a 15x128x120x160 FP16 tensor, for nothing.)
 __device__ __forceinline__ void acquire_partials() { asm volatile("" ::: "memory"); }
 
+// Keeps the computation of a value at this point of the program: the compiler would otherwise
+// sink it to its first use, behind the wait for a later load.  Emits no instruction.
+__device__ __forceinline__ void pin_here(float &v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin_here(unsigned &v) { asm volatile("" : "+v"(v)); }
+
 // Index of this wavefront in its block as a scalar: telling the compiler that it is uniform keeps
 // everything derived from it (the unit's slab, channel, pointers, loop bounds) in SGPRs.
 __device__ __forceinline__ unsigned wave_index() { return (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
@@ -226,6 +231,27 @@ __device__ __forceinline__ Chunk locate_chunk(const DevTensor &d, unsigned local
     c.channel = c.slab % d.channels;
     long long e0 = (long long)k * d.chunk;
     long long rem = d.inner - e0;
+    c.n = rem < (long long)d.chunk ? (int)rem : (int)d.chunk;
+    c.first = (long long)c.slab * d.inner + e0;
+    return c;
+}
+
+// The chunk of this block in a single-tensor launch.  Such a launch normally has a grid of
+// (chunks per slab, channels, outer), which names the chunk without any division (two integer
+// divisions sit between a block's start and its first load otherwise); tensors with more than
+// 65535 channels or outer slices keep the linear grid.  `unit` receives the chunk's linear index.
+__device__ __forceinline__ Chunk own_chunk(const DevTensor &d, unsigned &unit)
+{
+    if (!d.grid3) {
+        unit = blockIdx.x;
+        return locate_chunk(d, unit);
+    }
+    Chunk c;
+    c.channel = blockIdx.y;
+    c.slab = blockIdx.z * d.channels + blockIdx.y;
+    unit = c.slab * d.cps + blockIdx.x;
+    const long long e0 = (long long)blockIdx.x * d.chunk;
+    const long long rem = d.inner - e0;
     c.n = rem < (long long)d.chunk ? (int)rem : (int)d.chunk;
     c.first = (long long)c.slab * d.inner + e0;
     return c;
@@ -254,7 +280,7 @@ __device__ __forceinline__ QParams block_params(const DevTensor &d, float theta,
         bs.clip_active = sc.clip_active ? 1u : 0u;
     } else {
         __shared__ BlockScale shared_scale;
-        if ((threadIdx.x >> 6) == (blockIdx.x & (kBlock / 64 - 1))) {
+        if ((threadIdx.x >> 6) == ((blockIdx.x + blockIdx.y + blockIdx.z) & (kBlock / 64 - 1))) {
             const Scale sc = compute_scale<NEED_SIGMOID>(theta, d.eps, d.s_min, d.s_max);
             if ((threadIdx.x & 63) == 0) {
                 shared_scale.s = sc.s;
@@ -289,12 +315,11 @@ __device__ __forceinline__ void forward_elem(const T *x, T *y, int8_t *q, int i,
 // WRITE_Y: write the dequantized tensor y.  EMIT_Q: write the int8 codes, N per lane packed into
 // one 64-bit (FP16 input) or 32-bit (FP32 input) store.  At least one of the two.
 template <typename T, bool WRITE_Y, bool EMIT_Q, int G>
-__device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned unit)
+__device__ __forceinline__ void forward_chunk(const DevTensor &d, const Chunk &ck)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
     typedef unsigned QV __attribute__((ext_vector_type(N / 4)));
-    const Chunk ck = locate_chunk(d, unit);
     const T *x = (const T *)d.x + ck.first;
     T *y = WRITE_Y ? (T *)d.y + ck.first : nullptr;
     int8_t *q = EMIT_Q ? d.q + ck.first : nullptr;
@@ -375,9 +400,10 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, unsigned unit)
 template <typename T, int G>
 __device__ __forceinline__ void forward_variants(const DevTensor &d, unsigned unit)
 {
-    if (!d.q) forward_chunk<T, true, false, G>(d, unit);
-    else if (d.y) forward_chunk<T, true, true, G>(d, unit);
-    else forward_chunk<T, false, true, G>(d, unit);
+    const Chunk ck = locate_chunk(d, unit);
+    if (!d.q) forward_chunk<T, true, false, G>(d, ck);
+    else if (d.y) forward_chunk<T, true, true, G>(d, ck);
+    else forward_chunk<T, false, true, G>(d, ck);
 }
 
 // Tensors whose slabs are short (d.wave_units) give every wavefront a slab of its own: four
@@ -410,7 +436,20 @@ __device__ __forceinline__ double backward_elem(const T *x, const T *gy, T *gx, 
 }
 
 // Per-thread sum of gy*t over this thread's elements of the chunk (binary64).
-template <typename T, bool WRITE_GX, int G>
+//
+// SHORT selects the schedule for launches whose blocks are all resident at once (at most three per
+// compute unit: the 1x384x120x160 FP16 tensor).  Such a launch is one burst: every wavefront asks
+// for its whole chunk at the start, the data trickles in over the next microseconds, and whatever a
+// wavefront still has to compute after its last row has landed is added to the kernel's duration,
+// with nothing left to hide it.  So all x rows are requested before all gy rows; what depends on x
+// alone (quotient, clip, round, t, the mask: two thirds of the arithmetic) is done as the x rows
+// arrive, while the gy rows are still on their way; only the products and the selects wait for the
+// last row; and gx is stored at the very end, in one run, so that no store sits between the loads
+// in the memory pipeline.  The price is registers (every row's t is kept: 134 VGPRs instead of 71,
+// three wavefronts per SIMD), which costs a large launch more than the schedule gains (a
+// 15x128x120x160 FP16 tensor: 44.5 us instead of 40.7), so larger launches interleave as before.
+// The arithmetic and its order are the same in both schedules; so are the bits.
+template <typename T, bool WRITE_GX, int G, bool SHORT = false>
 __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk &ck, BlockScale &bs)
 {
     typedef typename VecOf<T>::type VT;
@@ -431,16 +470,30 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
     VT *ov = WRITE_GX ? (VT *)(gx + head) : nullptr;
 
     VT rx[kUnroll], rg[kUnroll];
-    if (nvec > 0) {
+    auto request = [&](int v0) {      // out-of-range lanes re-read the last vector
         const int last = nvec - 1;
+        if (SHORT) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            int v = u * G + tid;
-            v = v < last ? v : last;
-            rx[u] = ld_stream(xv + v);
-            rg[u] = ld_stream(gv + v);
+            for (int u = 0; u < kUnroll; ++u) {
+                const int v = v0 + u * G + tid;
+                rx[u] = ld_stream(xv + (v < last ? v : last));
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int v = v0 + u * G + tid;
+                rg[u] = ld_stream(gv + (v < last ? v : last));
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                int v = v0 + u * G + tid;
+                v = v < last ? v : last;
+                rx[u] = ld_stream(xv + v);
+                rg[u] = ld_stream(gv + v);
+            }
         }
-    }
+    };
+    if (nvec > 0) request(0);
 
     const QParams p = block_params<true, G>(d, theta, bs);
 
@@ -449,34 +502,67 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
     for (int u = 0; u < kUnroll; ++u) acc[u] = 0.0;
 
     for (int v0 = 0; v0 < nvec;) {
+        if (SHORT) {
+            float t[kUnroll][N];
+            unsigned inside[kUnroll], nan_row[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            int v = v0 + u * G + tid;
-            if (v < nvec) {
-                VT o;
-                bool any_nan = false;
+            for (int u = 0; u < kUnroll; ++u) {
+                inside[u] = 0u;
+                nan_row[u] = 0u;
 #pragma unroll
                 for (int e = 0; e < N; ++e) {
                     bool in_range, is_nan;
-                    float t = ste_terms((float)rx[u][e], p, in_range, is_nan);
-                    o[e] = in_range ? rg[u][e] : (T)0.0f;
-                    acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t, acc[u]);
-                    any_nan |= is_nan;
+                    t[u][e] = ste_terms((float)rx[u][e], p, in_range, is_nan);
+                    inside[u] |= in_range ? 1u << e : 0u;
+                    nan_row[u] |= is_nan ? 1u : 0u;
+                    pin_here(t[u][e]);
                 }
-                if (any_nan) acc[u] = __builtin_nan("");   // a NaN quotient poisons its channel
-                if (WRITE_GX) st_stream(ov + v, o);
+                pin_here(inside[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int v = v0 + u * G + tid;
+                if (v < nvec) {
+                    VT o;
+#pragma unroll
+                    for (int e = 0; e < N; ++e) {
+                        o[e] = (inside[u] >> e & 1u) ? rg[u][e] : (T)0.0f;
+                        acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t[u][e], acc[u]);
+                    }
+                    if (nan_row[u]) acc[u] = __builtin_nan("");   // a NaN quotient poisons its channel
+                    rg[u] = o;
+                }
+            }
+            if (WRITE_GX) {
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int v = v0 + u * G + tid;
+                    if (v < nvec) st_stream(ov + v, rg[u]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                int v = v0 + u * G + tid;
+                if (v < nvec) {
+                    VT o;
+                    bool any_nan = false;
+#pragma unroll
+                    for (int e = 0; e < N; ++e) {
+                        bool in_range, is_nan;
+                        float t = ste_terms((float)rx[u][e], p, in_range, is_nan);
+                        o[e] = in_range ? rg[u][e] : (T)0.0f;
+                        acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t, acc[u]);
+                        any_nan |= is_nan;
+                    }
+                    if (any_nan) acc[u] = __builtin_nan("");   // a NaN quotient poisons its channel
+                    if (WRITE_GX) st_stream(ov + v, o);
+                }
             }
         }
         v0 += kUnroll * G;
         if (v0 >= nvec) break;
-        const int last = nvec - 1;
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            int v = v0 + u * G + tid;
-            v = v < last ? v : last;
-            rx[u] = ld_stream(xv + v);
-            rg[u] = ld_stream(gv + v);
-        }
+        request(v0);
     }
 
     double sum = 0.0;
@@ -690,17 +776,16 @@ __device__ __forceinline__ unsigned combine(const DevTensor &d, const Chunk &ck,
 }
 
 // One block of the backward grid, owning one chunk of one slab.
-template <typename T, bool FUSED>
-__device__ __forceinline__ void backward_block(const DevTensor &d, unsigned local_block)
+template <typename T, bool FUSED, bool SHORT = false>
+__device__ __forceinline__ void backward_block(const DevTensor &d, const Chunk &ck, unsigned local_block)
 {
     __shared__ double wave_part[kBlock / 64];
     __shared__ double fin_part[kBlock / 64];
     __shared__ unsigned is_last;
 
-    const Chunk ck = locate_chunk(d, local_block);
     const bool write_gx = !(d.flags & 1u);
     BlockScale bs;
-    double sum = write_gx ? backward_chunk<T, true, kBlock>(d, ck, bs) : backward_chunk<T, false, kBlock>(d, ck, bs);
+    double sum = write_gx ? backward_chunk<T, true, kBlock, SHORT>(d, ck, bs) : backward_chunk<T, false, kBlock, SHORT>(d, ck, bs);
 
     sum = wave_sum(sum);
     if ((threadIdx.x & 63) == kSumLane) wave_part[threadIdx.x >> 6] = sum;
@@ -747,7 +832,7 @@ template <typename T, bool FUSED>
 __device__ __forceinline__ void backward_dispatch(const DevTensor &d, unsigned local_block)
 {
     if (d.wave_units) backward_waves<T, FUSED>(d, local_block);
-    else backward_block<T, FUSED>(d, local_block);
+    else backward_block<T, FUSED>(d, locate_chunk(d, local_block), local_block);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -792,9 +877,10 @@ __global__ void __launch_bounds__(kBlock) forward_kernel(const DevTensor d)
 {
     if (WAVES) {
         const unsigned unit = blockIdx.x * (kBlock / 64) + wave_index();
-        if (unit < d.slabs * d.cps) forward_chunk<T, WRITE_Y, EMIT_Q, 64>(d, unit);
+        if (unit < d.slabs * d.cps) forward_chunk<T, WRITE_Y, EMIT_Q, 64>(d, locate_chunk(d, unit));
     } else {
-        forward_chunk<T, WRITE_Y, EMIT_Q, kBlock>(d, blockIdx.x);
+        unsigned unit;
+        forward_chunk<T, WRITE_Y, EMIT_Q, kBlock>(d, own_chunk(d, unit));
     }
 }
 
@@ -811,22 +897,29 @@ __global__ void __launch_bounds__(kBlock) forward_multi_kernel(const DevTensor *
         if (d.wave_units) {
             const unsigned unit = local * (kBlock / 64) + wave_index();
             if (unit < d.slabs * d.cps) {
-                if (d.dtype == 0) forward_chunk<_Float16, true, false, 64>(d, unit);
-                else forward_chunk<float, true, false, 64>(d, unit);
+                if (d.dtype == 0) forward_chunk<_Float16, true, false, 64>(d, locate_chunk(d, unit));
+                else forward_chunk<float, true, false, 64>(d, locate_chunk(d, unit));
             }
         } else if (d.dtype == 0) {
-            forward_chunk<_Float16, true, false, kBlock>(d, local);
+            forward_chunk<_Float16, true, false, kBlock>(d, locate_chunk(d, local));
         } else {
-            forward_chunk<float, true, false, kBlock>(d, local);
+            forward_chunk<float, true, false, kBlock>(d, locate_chunk(d, local));
         }
     }
 }
 
-template <typename T, bool FUSED, bool WAVES>
+// SHAPE: 0 = one chunk per block; 1 = one slab per wavefront (short slabs); 2 = one chunk per block
+// in a launch of at most kShortLaunchBlocks blocks (see backward_chunk, SHORT).
+template <typename T, bool FUSED, int SHAPE>
 __global__ void __launch_bounds__(kBlock) backward_kernel(const DevTensor d)
 {
-    if (WAVES) backward_waves<T, FUSED>(d, blockIdx.x);
-    else backward_block<T, FUSED>(d, blockIdx.x);
+    if (SHAPE == 1) {
+        backward_waves<T, FUSED>(d, blockIdx.x);
+    } else {
+        unsigned unit;
+        const Chunk ck = own_chunk(d, unit);
+        backward_block<T, FUSED, SHAPE == 2>(d, ck, unit);
+    }
 }
 
 template <bool FUSED>
@@ -869,6 +962,50 @@ __global__ void __launch_bounds__(kBlock) fill_zero_kernel(unsigned *p, size_t w
 }
 
 }  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// Measurement aid (fq_probe_stream): streaming kernels with no arithmetic in the launch shape of the
+// forward and backward kernels (256-thread blocks, one chunk of kChunkVecs 128-bit vectors each,
+// every load issued before the first store, non-temporal).  What they take is what the memory
+// system and the launch cost alone take for the same bytes.
+namespace {
+typedef unsigned probe_vec __attribute__((ext_vector_type(4)));
+
+template <int INPUTS>
+__global__ void __launch_bounds__(kBlock) probe_kernel(const probe_vec *a, const probe_vec *b, probe_vec *out, size_t nvec)
+{
+    constexpr int kRows = kChunkVecs / kBlock;
+    if (INPUTS == 0) return;
+    const size_t first = (size_t)blockIdx.x * kChunkVecs + threadIdx.x;
+    probe_vec ra[kRows], rb[kRows];
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+        size_t v = first + (size_t)u * kBlock;
+        v = v < nvec ? v : nvec - 1;
+        ra[u] = ld_stream(a + v);
+        if (INPUTS == 2) rb[u] = ld_stream(b + v);
+    }
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+        const size_t v = first + (size_t)u * kBlock;
+        if (v < nvec) st_stream(out + v, INPUTS == 2 ? ra[u] ^ rb[u] : ra[u]);
+    }
+}
+}  // namespace
+
+int launch_probe(int inputs, const void *a, const void *b, void *out, size_t bytes, void *stream)
+{
+    const size_t nvec = bytes / kVecBytes;
+    if (nvec == 0) return 0;
+    const unsigned blocks = (unsigned)((nvec + kChunkVecs - 1) / kChunkVecs);
+    hipStream_t st = (hipStream_t)stream;
+    const probe_vec *pa = (const probe_vec *)a, *pb = (const probe_vec *)b;
+    probe_vec *po = (probe_vec *)out;
+    if (inputs == 0) hipLaunchKernelGGL(probe_kernel<0>, dim3(blocks), dim3(kBlock), 0, st, pa, pb, po, nvec);
+    else if (inputs == 1) hipLaunchKernelGGL(probe_kernel<1>, dim3(blocks), dim3(kBlock), 0, st, pa, pb, po, nvec);
+    else hipLaunchKernelGGL(probe_kernel<2>, dim3(blocks), dim3(kBlock), 0, st, pa, pb, po, nvec);
+    return (int)hipGetLastError();
+}
 
 // ---------------------------------------------------------------------------------------------
 // Built-in scratch memory for callers that cannot allocate (fq_backward_static).  One array per
@@ -916,12 +1053,20 @@ static void launch(K kernel, unsigned blocks, hipStream_t st, Args... args)
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kBlock), 0, st, args...);
 }
 
+// Single-tensor launch: grid (chunks per slab, channels, outer) where d.grid3 says so.
+template <typename K>
+static void launch_tensor(K kernel, unsigned blocks, hipStream_t st, const DevTensor &d)
+{
+    const dim3 grid = d.grid3 ? dim3(d.cps, d.channels, d.outer) : dim3(blocks);
+    hipLaunchKernelGGL(kernel, grid, dim3(kBlock), 0, st, d);
+}
+
 template <typename T, bool WAVES>
 static void launch_forward_single(const DevTensor &d, unsigned blocks, hipStream_t st)
 {
-    if (!d.q) launch(forward_kernel<T, true, false, WAVES>, blocks, st, d);
-    else if (d.y) launch(forward_kernel<T, true, true, WAVES>, blocks, st, d);
-    else launch(forward_kernel<T, false, true, WAVES>, blocks, st, d);
+    if (!d.q) launch_tensor(forward_kernel<T, true, false, WAVES>, blocks, st, d);
+    else if (d.y) launch_tensor(forward_kernel<T, true, true, WAVES>, blocks, st, d);
+    else launch_tensor(forward_kernel<T, false, true, WAVES>, blocks, st, d);
 }
 
 int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream)
@@ -940,22 +1085,25 @@ int launch_forward(const KArgs &a, unsigned blocks, bool emit_q, void *stream)
     return (int)hipGetLastError();
 }
 
-template <typename T, bool WAVES>
+template <typename T, int SHAPE>
 static void launch_backward_typed(const DevTensor &d, unsigned blocks, bool fused_finalize, hipStream_t st)
 {
-    if (fused_finalize) launch(backward_kernel<T, true, WAVES>, blocks, st, d);
-    else launch(backward_kernel<T, false, WAVES>, blocks, st, d);
+    if (fused_finalize) launch_tensor(backward_kernel<T, true, SHAPE>, blocks, st, d);
+    else launch_tensor(backward_kernel<T, false, SHAPE>, blocks, st, d);
+}
+
+template <typename T>
+static void launch_backward_shaped(const DevTensor &d, unsigned blocks, bool fused_finalize, hipStream_t st)
+{
+    if (d.wave_units) launch_backward_typed<T, 1>(d, blocks, fused_finalize, st);
+    else if (blocks <= kShortLaunchBlocks) launch_backward_typed<T, 2>(d, blocks, fused_finalize, st);
+    else launch_backward_typed<T, 0>(d, blocks, fused_finalize, st);
 }
 
 static void launch_backward_single(const DevTensor &d, unsigned blocks, bool fused_finalize, hipStream_t st)
 {
-    if (d.dtype == 0) {
-        if (d.wave_units) launch_backward_typed<_Float16, true>(d, blocks, fused_finalize, st);
-        else launch_backward_typed<_Float16, false>(d, blocks, fused_finalize, st);
-    } else {
-        if (d.wave_units) launch_backward_typed<float, true>(d, blocks, fused_finalize, st);
-        else launch_backward_typed<float, false>(d, blocks, fused_finalize, st);
-    }
+    if (d.dtype == 0) launch_backward_shaped<_Float16>(d, blocks, fused_finalize, st);
+    else launch_backward_shaped<float>(d, blocks, fused_finalize, st);
 }
 
 int launch_backward(const KArgs &a, unsigned blocks, bool fused_finalize, void *stream)
