@@ -221,7 +221,7 @@ void fq_plan_destroy(fq_plan *plan);
 
 /*
  * Distillation loss between one student and one teacher feature map, and its gradient with
- * respect to the student (Sec. 3.1, Eq. (7)): the producer of the gy that fq_backward consumes.
+ * respect to the student (Sec. 3.2, Eq. (7)): the producer of the gy that fq_backward consumes.
  *   mse   = mean over all n*channels*inner elements of (a - b)^2
  *   cos_p = <a_p, b_p> / (max(||a_p||, eps) * max(||b_p||, eps))   per position p = (n, m), the
  *           inner product and the norms running over the channel axis
@@ -233,8 +233,8 @@ void fq_plan_destroy(fq_plan *plan);
  * gstudent = upstream * dloss/dstudent in the tensors' dtype (rounded once from binary64; a
  * clamped norm counts as a constant).  `upstream` is the factor in front of this pair's loss in
  * the total (Eq. (7) sums the pairs: 1, or the loss scale of an FP16 run).  student / teacher are
- * contiguous [n, channels, inner]; gstudent may be exactly student or teacher (in place).  Two
- * launches; no atomics, fixed summation order.  A tensor without elements needs no workspace and
+ * contiguous [n, channels, inner]; gstudent may be exactly student or teacher (in place).  Two or
+ * three launches; no atomics, fixed summation order.  A tensor without elements needs no workspace and
  * gives NaN for mse and loss (a mean of nothing); cosim is then NaN without positions and 0 with
  * positions but no channels.  The workspace need not be initialised and may be shared with other calls
  * that do not overlap in time.
@@ -248,6 +248,12 @@ typedef struct fq_distill {
     double *out;                      /* out: 3 doubles, 8-byte aligned */
 } fq_distill;
 size_t fq_distill_workspace_bytes(const fq_distill *d);   /* 0 if d does not validate; host only */
+/* How often fq_distill_loss reads the pair from memory for this descriptor: 1 (one fused kernel
+   holds a tile of the pair in registers from the statistics to the gradient: up to 512 channels,
+   inner a multiple of 4, pointers aligned to 4 elements; also when no gradient is asked for) or 2
+   (a statistics kernel, then a gradient kernel); 0 if d does not validate or has no elements.
+   Pure host function. */
+int fq_distill_reads_of_pair(const fq_distill *d);
 fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes, void *hip_stream);
 
 /*

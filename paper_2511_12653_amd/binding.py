@@ -176,6 +176,8 @@ _lib.fq_distill_workspace_bytes.argtypes = [ctypes.POINTER(FqDistill)]
 _lib.fq_distill_workspace_bytes.restype = ctypes.c_size_t
 _lib.fq_distill_loss.argtypes = [ctypes.POINTER(FqDistill), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fq_distill_loss.restype = ctypes.c_int
+_lib.fq_distill_reads_of_pair.argtypes = [ctypes.POINTER(FqDistill)]
+_lib.fq_distill_reads_of_pair.restype = ctypes.c_int
 _lib.fq_layout.argtypes = [ctypes.POINTER(FqTensor), ctypes.POINTER(FqLayoutInfo)]
 _lib.fq_layout.restype = ctypes.c_int
 _lib.fq_status_string.argtypes = [ctypes.c_int]
@@ -286,6 +288,10 @@ def fq_plan_destroy(plan):
 
 def fq_distill_workspace_bytes(d: FqDistill) -> int:
     return int(_lib.fq_distill_workspace_bytes(ctypes.byref(d)))
+
+
+def fq_distill_reads_of_pair(d: FqDistill) -> int:
+    return int(_lib.fq_distill_reads_of_pair(ctypes.byref(d)))
 
 
 def fq_distill_loss(d: FqDistill, workspace, stream=None):

@@ -1,19 +1,29 @@
 // Distillation loss between a student and a teacher feature map and its gradient with respect to
-// the student (DPVO-QAT++ Sec. 3.1, Eq. (7): MSE plus lambda times one minus the cosine
+// the student (DPVO-QAT++ Sec. 3.2, Eq. (7): MSE plus lambda times one minus the cosine
 // similarity over the channel axis, averaged over positions).  This is the producer of the
 // upstream gradient that the fake-quantization backward consumes.
 //
 // [N, C, M] tensors; a "position" is one (n, m).  The reduction runs ACROSS the channel axis, whose
-// stride is M elements, so the layout is read the way it lies in memory: a wavefront owns 64
-// lanes x V consecutive positions of one image (one coalesced row per channel) and walks over a
-// group of channels, every lane keeping the four sums of its V positions (a.b, a.a, b.b,
-// (a-b)^2) in binary64 registers.  No transposition, no atomics:
+// stride is M elements, so the layout is read the way it lies in memory, without transposition and
+// without atomics.  Two ways, chosen on the host:
+//
+// One read of the pair (fused kernel; channel counts up to 512, M a multiple of 4): a block owns a
+// tile of all channels x one 128-byte run of positions (64 FP16 or 32 FP32 positions); a lane holds
+// 4 consecutive positions of up to 16 channels IN REGISTERS, adds its four sums (a.b, a.a, b.b,
+// (a-b)^2) per position, the block adds the lanes' sums through LDS in a fixed order, forms cos and
+// the two gradient coefficients per position, and every lane then writes the gradient of the
+// elements it still holds.  HBM traffic: read a, read b, write ga -- the algorithmic 3 bytes-widths
+// per element.
+//
+// Two reads (any shape): a wavefront owns 64 lanes x V consecutive positions (one coalesced row per
+// channel) and walks over a group of channels, every lane keeping the four sums of its V positions
+// in binary64 registers:
 //   stats kernel   one block per position tile, one wavefront per channel group (up to 16); the
 //                  wavefronts add their sums through LDS in a fixed tree, then the block forms
 //                  cos and the two coefficients of the gradient for its positions and leaves
 //                  its sums of cos and of the squared error
-//   grad kernel    elementwise: ga = k1 (a - b) - cB b + cA a, rounded once to the I/O type;
-//                  its first wavefront also adds the block sums in index order into the 3 results
+//   grad kernel    elementwise: ga = k1 (a - b) - cB b + cA a, rounded once to the I/O type
+// In both, the last small step adds the per-block sums in index order into the 3 results.
 // All arithmetic is binary64 (two conversions and five fused multiply-adds per element pair, well
 // under the memory time), so results do not depend on how the channels were grouped beyond
 // rounding at the 1e-16 level, and are reproducible run to run.
@@ -234,15 +244,29 @@ __global__ __launch_bounds__(1024) void distill_stats_kernel(DistillArgs k)
     }
 }
 
-// The three results from the per-block sums, added in index order by one wavefront.
+// The three results from the per-block sums, added in a fixed order by one wavefront: lane l takes
+// the sums l, l + 64, l + 128, ... (eight loads in flight at a time: thousands of tiles would
+// otherwise be as many dependent round trips to memory), then the lanes are added by wave_sum.
 __device__ __forceinline__ void finish(const DistillArgs &k)
 {
     const unsigned lane = threadIdx.x & 63;
     double sc = 0.0, ss = 0.0;
-    for (unsigned i = lane; i < k.tiles; i += 64) {
-        const double2v v = ld_global((const double2v *)k.blocksum + i);
-        sc += v[0];
-        ss += v[1];
+    constexpr unsigned kBatch = 8;
+    for (unsigned i0 = lane; i0 < k.tiles; i0 += 64 * kBatch) {
+        double2v v[kBatch];
+#pragma unroll
+        for (unsigned j = 0; j < kBatch; ++j) {
+            const unsigned i = i0 + 64 * j;
+            v[j] = double2v{0.0, 0.0};
+            if (i < k.tiles) v[j] = ld_global((const double2v *)k.blocksum + i);
+        }
+#pragma unroll
+        for (unsigned j = 0; j < kBatch; ++j) {
+            if (i0 + 64 * j < k.tiles) {
+                sc += v[j][0];
+                ss += v[j][1];
+            }
+        }
     }
     sc = wave_sum(sc);
     ss = wave_sum(ss);
@@ -254,7 +278,49 @@ __device__ __forceinline__ void finish(const DistillArgs &k)
     }
 }
 
-__global__ __launch_bounds__(64) void distill_finish_kernel(DistillArgs k) { finish(k); }
+// The same as a kernel of its own, by one block of 1024 threads: thread t takes the sums t,
+// t + 1024, ..., the wavefronts add their lanes (wave_sum), thread 0 adds the sixteen wavefront
+// sums in index order.
+__global__ __launch_bounds__(1024) void distill_finish_kernel(DistillArgs k)
+{
+    __shared__ double part[2 * 16];
+    double sc = 0.0, ss = 0.0;
+    constexpr unsigned kBatch = 4;
+    for (unsigned i0 = threadIdx.x; i0 < k.tiles; i0 += 1024 * kBatch) {
+        double2v v[kBatch];
+#pragma unroll
+        for (unsigned j = 0; j < kBatch; ++j) {
+            const unsigned i = i0 + 1024 * j;
+            v[j] = double2v{0.0, 0.0};
+            if (i < k.tiles) v[j] = ld_global((const double2v *)k.blocksum + i);
+        }
+#pragma unroll
+        for (unsigned j = 0; j < kBatch; ++j) {
+            if (i0 + 1024 * j < k.tiles) {
+                sc += v[j][0];
+                ss += v[j][1];
+            }
+        }
+    }
+    sc = wave_sum(sc);
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == kSumLane) {
+        part[threadIdx.x >> 6] = sc;
+        part[16 + (threadIdx.x >> 6)] = ss;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        sc = ss = 0.0;
+        for (unsigned w = 0; w < 16; ++w) {
+            sc += part[w];
+            ss += part[16 + w];
+        }
+        const double mse = ss * k.inv_ncm, cosim = sc * k.inv_nm;
+        st_global(k.out + 0, mse);
+        st_global(k.out + 1, cosim);
+        st_global(k.out + 2, mse + k.lambda * (1.0 - cosim));
+    }
+}
 
 template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void distill_grad_kernel(DistillArgs k, unsigned groups, unsigned per_group)
@@ -313,13 +379,166 @@ __global__ __launch_bounds__(kThreads) void distill_grad_kernel(DistillArgs k, u
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// One read of the pair.  Block: kFusedThreads threads = R rows of L lanes; lane l of row r holds
+// positions 4l .. 4l+3 of the tile for channels r, r + R, r + 2R, ... (KCH of them at most).
+constexpr int kFusedThreads = 512;
+constexpr int kFusedVec = 4;                     // positions per lane
+constexpr int kFusedMaxKch = 16;                 // channels per lane the registers hold (FP16; half for FP32)
+// A tile's rows are 128 bytes of each channel, a whole cache line.  (Rows of 64 bytes would cut a
+// 1x384x120x160 pair into 600 tiles instead of 300 and spread them more evenly over the 256
+// compute units, but half-line accesses cost more than the balance gains: 24.4 us against 16.9.)
+template <typename T> struct FusedShape {
+    static constexpr int L = 128 / (kFusedVec * (int)sizeof(T));   // lanes per row: 16 (FP16), 8 (FP32)
+    static constexpr int P = kFusedVec * L;                        // positions per tile: 64 / 32
+    static constexpr int R = kFusedThreads / L;                    // channel rows: 32 / 64
+};
+
+template <typename T, int KCH, bool WANT_GRAD>
+__global__ __launch_bounds__(kFusedThreads, 4) void distill_fused_kernel(DistillArgs k)
+{
+    typedef FusedShape<T> Shape;
+    constexpr int V = kFusedVec, L = Shape::L, P = Shape::P, R = Shape::R;
+    typedef typename Pack<T, V>::type VT;
+    __shared__ double red[8 * kFusedThreads];     // half of the lanes' sums at a time: [value][thread]
+    __shared__ double stat[P * 4];                // per position: a.b, a.a, b.b, (a-b)^2
+    __shared__ double coefs[P * 2];               // per position: the two gradient coefficients
+
+    const unsigned lane = threadIdx.x % L, row = threadIdx.x / L;
+    const unsigned tile = blockIdx.x;
+    const unsigned n = tile / k.tiles_per_n, tn = tile - n * k.tiles_per_n;
+    const long long tile_m = (long long)tn * P;
+    long long m0 = tile_m + (long long)lane * V;
+    const bool lane_valid = m0 < k.M;
+    if (!lane_valid) m0 = k.M - V;                // lanes past the end re-read the last quad; results dropped
+    const long long base = (long long)n * k.C * k.M + m0;
+    const T *a = (const T *)k.a + base;
+    const T *b = (const T *)k.b + base;
+
+    VT ra[KCH], rb[KCH];
+#pragma unroll
+    for (int j = 0; j < KCH; ++j) {
+        unsigned c = row + (unsigned)j * R;
+        c = c < k.C ? c : k.C - 1;                // rows past the last channel re-read it; results dropped
+        ra[j] = ld_stream((const VT *)(a + (long long)c * k.M));
+        rb[j] = ld_stream((const VT *)(b + (long long)c * k.M));
+    }
+
+    double acc[V * 4];
+#pragma unroll
+    for (int i = 0; i < V * 4; ++i) acc[i] = 0.0;
+#pragma unroll
+    for (int j = 0; j < KCH; ++j) {
+        if (row + (unsigned)j * R < k.C) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const double x = (double)(float)ra[j][e];
+                const double y = (double)(float)rb[j][e];
+                const double d = x - y;
+                acc[e * 4 + 0] = __builtin_fma(x, y, acc[e * 4 + 0]);
+                acc[e * 4 + 1] = __builtin_fma(x, x, acc[e * 4 + 1]);
+                acc[e * 4 + 2] = __builtin_fma(y, y, acc[e * 4 + 2]);
+                acc[e * 4 + 3] = __builtin_fma(d, d, acc[e * 4 + 3]);
+            }
+        }
+    }
+
+    // Sum over the R rows, in row order, eight of the sixteen values at a time.
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) red[i * kFusedThreads + threadIdx.x] = acc[half * 8 + i];
+        __syncthreads();
+        if (threadIdx.x < 8 * L) {
+            const unsigned i = threadIdx.x / L, l = threadIdx.x % L;
+            double sum = 0.0;
+            for (unsigned r = 0; r < (unsigned)R; ++r) sum += red[i * kFusedThreads + r * L + l];
+            const unsigned value = half * 8 + i;                 // = e * 4 + which sum
+            stat[(l * V + value / 4) * 4 + value % 4] = sum;
+        }
+        __syncthreads();
+    }
+
+    // One thread per position (all in the first wavefront): cos, the gradient's coefficients, and
+    // the tile's sums of cos and of the squared error.
+    if (threadIdx.x < 64) {
+        double cos_sum = 0.0, sq_sum = 0.0;
+        const unsigned pp = threadIdx.x;
+        if (pp < (unsigned)P && tile_m + pp < k.M) {
+            const double dot = stat[pp * 4 + 0], na = stat[pp * 4 + 1], nb = stat[pp * 4 + 2];
+            const double ra_ = sqrt(na), rb_ = sqrt(nb);
+            // a NaN norm stays NaN, so a non-finite input poisons its whole position visibly
+            const double ca = ra_ < k.eps ? k.eps : ra_, cb = rb_ < k.eps ? k.eps : rb_;
+            const double inv = 1.0 / (ca * cb);
+            const double cosp = dot / (ca * cb);
+            const double self = ra_ > k.eps ? cosp / na : 0.0;
+            coefs[pp * 2 + 0] = k.k2u * inv;
+            coefs[pp * 2 + 1] = k.k2u * self;
+            cos_sum = cosp;
+            sq_sum = stat[pp * 4 + 3];
+        }
+        cos_sum = wave_sum(cos_sum);
+        sq_sum = wave_sum(sq_sum);
+        if (threadIdx.x == kSumLane) {
+            double2v o = {cos_sum, sq_sum};
+            st_global((double2v *)k.blocksum + tile, o);
+        }
+    }
+    if (!WANT_GRAD) return;
+    __syncthreads();
+
+    if (!lane_valid) return;
+    double cb[V], ca[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        cb[e] = coefs[(lane * V + e) * 2 + 0];
+        ca[e] = coefs[(lane * V + e) * 2 + 1];
+    }
+    T *ga = (T *)k.ga + base;
+#pragma unroll
+    for (int j = 0; j < KCH; ++j) {
+        const unsigned c = row + (unsigned)j * R;
+        if (c < k.C) {
+            VT o;
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const double x = (double)(float)ra[j][e];
+                const double y = (double)(float)rb[j][e];
+                double g = k.k1u * (x - y);
+                g = __builtin_fma(-cb[e], y, g);
+                g = __builtin_fma(ca[e], x, g);
+                o[e] = (T)(float)g;
+            }
+            st_stream((VT *)(ga + (long long)c * k.M), o);
+        }
+    }
+}
+
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Plan {
     int vec;                 // elements per lane
+    int fused_kch;           // > 0: the fused kernel with this many channels per lane; 0: two kernels
     unsigned tiles_per_n, tiles, groups, per_group, grad_groups, grad_per_group;
     size_t stats_lds, off_blocksum, bytes;
 };
+
+// Channels per lane the fused kernel would need for this pair, rounded up to a width it is built
+// for; 0 if the pair does not qualify (positions not in whole quads, a pointer off the quad's
+// alignment, or more channels than a lane's registers hold).
+int fused_channels_per_lane(const fq_distill *d)
+{
+    const size_t esz = d->dtype == FQ_F16 ? 2 : 4;
+    const uintptr_t addr_bits = (uintptr_t)d->student | (uintptr_t)d->teacher | (uintptr_t)d->gstudent;
+    if (d->inner % kFusedVec || addr_bits % (kFusedVec * esz)) return 0;
+    const long long rows = d->dtype == FQ_F16 ? FusedShape<_Float16>::R : FusedShape<float>::R;
+    const long long need = (d->channels + rows - 1) / rows;
+    const long long cap = d->dtype == FQ_F16 ? kFusedMaxKch : kFusedMaxKch / 2;
+    if (need > cap) return 0;
+    for (int kch : {2, 4, 6, 8, 12, 16})
+        if (kch >= need) return kch;
+    return 0;
+}
 
 fq_status make_plan(const fq_distill *d, Plan &pl)
 {
@@ -355,6 +574,21 @@ fq_status make_plan(const fq_distill *d, Plan &pl)
         pl = Plan{};
         pl.vec = 1;
         pl.bytes = 256;
+        return FQ_OK;
+    }
+    pl.fused_kch = fused_channels_per_lane(d);
+    if (pl.fused_kch) {
+        const long long per_tile = d->dtype == FQ_F16 ? FusedShape<_Float16>::P : FusedShape<float>::P;
+        const long long tpn = (d->inner + per_tile - 1) / per_tile;
+        if (tpn * d->n > 0x3fffffffLL) return FQ_ERR_SHAPE;
+        pl.vec = kFusedVec;
+        pl.tiles_per_n = (unsigned)tpn;
+        pl.tiles = (unsigned)(tpn * d->n);
+        pl.groups = pl.per_group = pl.grad_groups = pl.grad_per_group = 0;
+        pl.stats_lds = 0;
+        pl.off_blocksum = 0;                       // no per-position coefficients leave the block
+        pl.bytes = align256((size_t)pl.tiles * 2 * sizeof(double));
+        if (pl.bytes < 256) pl.bytes = 256;
         return FQ_OK;
     }
     const int full = (int)(kVecBytes / esz) < kMaxVec ? (int)(kVecBytes / esz) : kMaxVec;
@@ -417,15 +651,47 @@ fq_status launch(const DistillArgs &k, const Plan &pl, bool want_grad, hipStream
         const unsigned grad_blocks = (pl.tiles * pl.grad_groups + kWaves - 1) / kWaves;
         distill_grad_kernel<T, V><<<grad_blocks, kThreads, 0, st>>>(k, pl.grad_groups, pl.grad_per_group);
     } else {
-        distill_finish_kernel<<<1, 64, 0, st>>>(k);
+        distill_finish_kernel<<<1, 1024, 0, st>>>(k);
     }
     return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_LAUNCH;
+}
+
+template <typename T, int KCH>
+fq_status launch_fused(const DistillArgs &k, const Plan &pl, bool want_grad, hipStream_t st)
+{
+    if (want_grad) distill_fused_kernel<T, KCH, true><<<pl.tiles, kFusedThreads, 0, st>>>(k);
+    else distill_fused_kernel<T, KCH, false><<<pl.tiles, kFusedThreads, 0, st>>>(k);
+    distill_finish_kernel<<<1, 1024, 0, st>>>(k);
+    return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_LAUNCH;
+}
+
+template <typename T>
+fq_status launch_fused_width(const DistillArgs &k, const Plan &pl, bool want_grad, hipStream_t st)
+{
+    switch (pl.fused_kch) {
+    case 2: return launch_fused<T, 2>(k, pl, want_grad, st);
+    case 4: return launch_fused<T, 4>(k, pl, want_grad, st);
+    case 6: return launch_fused<T, 6>(k, pl, want_grad, st);
+    case 8: return launch_fused<T, 8>(k, pl, want_grad, st);
+    default: break;
+    }
+    if (sizeof(T) == 2 && pl.fused_kch == 12) return launch_fused<_Float16, 12>(k, pl, want_grad, st);
+    if (sizeof(T) == 2 && pl.fused_kch == 16) return launch_fused<_Float16, 16>(k, pl, want_grad, st);
+    return FQ_ERR_SHAPE;                           // not reached: make_plan offers only the widths above
 }
 
 }  // namespace
 }  // namespace fq
 
 extern "C" {
+
+int fq_distill_reads_of_pair(const fq_distill *d)
+{
+    fq::Plan pl;
+    if (fq::make_plan(d, pl) != FQ_OK) return 0;
+    if (d->n * d->inner == 0 || d->channels == 0) return 0;
+    return pl.fused_kch ? 1 : (d->gstudent ? 2 : 1);
+}
 
 size_t fq_distill_workspace_bytes(const fq_distill *d)
 {
@@ -470,6 +736,11 @@ fq_status fq_distill_loss(const fq_distill *d, void *workspace, size_t ws_bytes,
     k.inv_ncm = 1.0 / ncm;
     k.inv_nm = 1.0 / nm;
     const bool grad = d->gstudent != nullptr;
+    if (pl.fused_kch) {
+        k.coef = nullptr;
+        return d->dtype == FQ_F16 ? launch_fused_width<_Float16>(k, pl, grad, st)
+                                  : launch_fused_width<float>(k, pl, grad, st);
+    }
     if (d->dtype == FQ_F16) {
         switch (pl.vec) {
         case 4: return launch<_Float16, 4>(k, pl, grad, st);

@@ -153,17 +153,31 @@ def _distill(fq, **kw):
 
 def test_distill_struct_and_workspace(fq):
     assert ctypes.sizeof(fq.FqDistill) == 3 * 8 + 4 * 4 + 4 * 8
-    # coefficients (2 doubles per position) + per-tile sums (2 doubles per tile of 64 x 2 positions:
-    # one image of 19200 positions is cut into 150 tiles of 128 positions)
+    # 384 channels, inner a multiple of 4, aligned: the fused kernel reads the pair once and needs
+    # only per-tile sums (2 doubles per tile of 64 FP16 positions: 300 tiles per image)
+    assert fq.fq_distill_reads_of_pair(_distill(fq)) == 1
+    got = fq.fq_distill_workspace_bytes(_distill(fq))
+    assert got % 256 == 0 and 300 * 16 <= got < 300 * 16 + 256
+    got = fq.fq_distill_workspace_bytes(_distill(fq, n=15))
+    assert 15 * 300 * 16 <= got < 15 * 300 * 16 + 256
+    assert fq.fq_distill_reads_of_pair(_distill(fq, gstudent=None)) == 1
+    # more channels than a lane's registers hold (or inner not in whole quads, or pointers off the
+    # quad's alignment): statistics kernel + gradient kernel, coefficients (2 doubles per position)
+    # + per-tile sums (2 doubles per tile of 64 x 2 positions: 150 tiles of 128 positions)
+    for kw in (dict(channels=520), dict(inner=19202), dict(student=0x10000002)):
+        assert fq.fq_distill_reads_of_pair(_distill(fq, **kw)) == 2
+        assert fq.fq_distill_reads_of_pair(_distill(fq, gstudent=None, **kw)) == 1
     P = 19200
     want = P * 16 + 150 * 16
-    got = fq.fq_distill_workspace_bytes(_distill(fq))
+    got = fq.fq_distill_workspace_bytes(_distill(fq, channels=520))
     assert got % 256 == 0 and want <= got < want + 2 * 256
     # a batch of 15 images: 15 * 75 tiles of 256 positions
     P = 15 * 19200
     want = P * 16 + 15 * 75 * 16
-    got = fq.fq_distill_workspace_bytes(_distill(fq, n=15))
+    got = fq.fq_distill_workspace_bytes(_distill(fq, n=15, channels=520, student=1 << 40, teacher=2 << 40,
+                                                 gstudent=3 << 40))
     assert want <= got < want + 2 * 256
+    assert fq.fq_distill_reads_of_pair(_distill(fq, dtype=7)) == 0 and fq.fq_distill_reads_of_pair(_distill(fq, n=0)) == 0
     # empty tensors validate and need only the minimum
     assert fq.fq_distill_workspace_bytes(_distill(fq, n=0)) == 256
     assert fq.fq_distill_workspace_bytes(_distill(fq, channels=0, student=None, teacher=None)) == 256

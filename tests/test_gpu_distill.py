@@ -59,6 +59,13 @@ def _run(a, b, lam, oracle, eps=1e-8, upstream=1.0, want_grad=True, inplace=None
     d = fq.FqDistill.from_torch(n, c, m, da, db, out, dg, lam=lam, eps=eps, upstream=upstream)
     need = fq.fq_distill_workspace_bytes(d)
     assert need >= 256 and need % 256 == 0
+    if a.size:
+        # which way the library takes is a function of shape and alignment: one fused kernel that
+        # reads the pair once, or a statistics kernel followed by a gradient kernel
+        rows = 32 if a.dtype == np.float16 else 64
+        fused = (m % 4 == 0 and (misalign * a.itemsize) % (4 * a.itemsize) == 0 and
+                 -(-c // rows) <= (16 if a.dtype == np.float16 else 8))
+        assert fq.fq_distill_reads_of_pair(d) == (1 if fused or not want_grad else 2), (label, a.shape, misalign)
     # the workspace need not be initialised: poison it
     ws = torch.full((need // 8,), float("nan"), dtype=torch.float64, device="cuda")
     fq.fq_distill_loss(d, ws)
@@ -104,6 +111,16 @@ def test_vector_path(oracle, dtype, shape):
 def test_scalar_path(oracle, dtype, shape, misalign):
     a, b = _pair(12, shape, dtype)
     _run(a, b, 1.0, oracle, misalign=misalign, label="scalar")
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("shape", [(1, 600, 256), (2, 1030, 64), (1, 512, 128), (1, 385, 64), (3, 200, 36),
+                                   (1, 64, 4), (2, 33, 124)])
+def test_channel_counts_around_the_fused_kernel_limits(oracle, dtype, shape):
+    """Channel counts on both sides of what a lane's registers hold (512 channels: 16 per lane for
+    FP16, 8 for FP32), every register width of the fused kernel, and ragged last tiles."""
+    a, b = _pair(21, shape, dtype)
+    _run(a, b, 0.5, oracle, label="limits")
 
 
 def test_random_shapes(oracle):
@@ -195,7 +212,7 @@ def test_full_size_feature_maps(oracle, shape):
 
 def test_feeds_the_fake_quantization_backward(oracle):
     """Loss gradient -> gy of fq_backward on the same stream, no host round trip: the chain the
-    distillation step runs (Sec. 3.1)."""
+    distillation step runs (Sec. 3.2)."""
     rng = np.random.Generator(np.random.Philox(19))
     n, c, m = 2, 24, 640
     x = (rng.standard_normal((n, c, m)) * 1.2).astype(np.float16)
