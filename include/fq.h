@@ -4,7 +4,10 @@
  * C ABI.  Every tensor pointer in fq_tensor is a DEVICE pointer owned by the
  * caller; descriptor structs and arrays of them are HOST memory.  The library
  * enqueues kernels on the given HIP stream and returns; it never synchronises
- * the device and never allocates or frees device memory.  All functions return
+ * the device and never allocates or frees device memory.  (The three calls that
+ * copy a descriptor table to the device -- fq_multi_tensor, fq_plan_create,
+ * fq_plan_run_adam -- stage it in pinned HOST memory; see fq_multi_tensor for
+ * what that implies.)  All functions return
  * an fq_status (0 = success, negative = failure); validation happens before
  * anything is enqueued, so a failing call has no device side effects.  Nothing
  * throws or aborts across this boundary.
@@ -187,6 +190,15 @@ fq_status fq_backward_static(const fq_tensor *t, void *hip_stream);
  * (Sec. 3.3).  `ts` is a host array of n descriptors; it is copied to the start of the
  * workspace on `stream` and may be reused as soon as the call returns.  n = 0 is a no-op.
  * FQ_FLAG_TWO_PASS on any tensor selects the two-launch backward for the whole list.
+ *
+ * Host-side behaviour of the table copy (also in fq_plan_create and, when the step changes, in
+ * fq_plan_run_adam): the table is staged in one of eight pinned host buffers that the library
+ * keeps for the life of the process.  A buffer is allocated (hipHostMalloc) the first time it is
+ * used or when a larger table comes along, and a call that finds its buffer still being read by a
+ * copy enqueued eight such calls earlier waits on the host for that one copy to finish
+ * (hipEventSynchronize); no other call of the library ever blocks.  Because of the allocation and
+ * the possible wait these three calls must not be made while a stream is being captured into a
+ * HIP graph: capture fq_plan_run (or the single-tensor calls) instead.
  */
 fq_status fq_multi_tensor(const fq_tensor *ts, int n, int mode,
                           void *workspace, size_t ws_bytes, void *hip_stream);
