@@ -280,7 +280,9 @@ __device__ __forceinline__ QParams block_params(const DevTensor &d, float theta,
         bs.clip_active = sc.clip_active ? 1u : 0u;
     } else {
         __shared__ BlockScale shared_scale;
-        if ((threadIdx.x >> 6) == ((blockIdx.x + blockIdx.y + blockIdx.z) & (kBlock / 64 - 1))) {
+        // (the block's linear index in the grid, whatever the grid's shape)
+        const unsigned linear = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+        if ((threadIdx.x >> 6) == (linear & (kBlock / 64 - 1))) {
             const Scale sc = compute_scale<NEED_SIGMOID>(theta, d.eps, d.s_min, d.s_max);
             if ((threadIdx.x & 63) == 0) {
                 shared_scale.s = sc.s;
@@ -436,9 +438,86 @@ __device__ __forceinline__ double backward_elem(const T *x, const T *gy, T *gx, 
 }
 
 // Per-thread sum of gy*t over this thread's elements of the chunk (binary64).
-//
-// SHORT selects the schedule for launches whose blocks are all resident at once (at most three per
-// compute unit: the 1x384x120x160 FP16 tensor).  Such a launch is one burst: every wavefront asks
+template <typename T, bool WRITE_GX, int G>
+__device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk &ck, BlockScale &bs)
+{
+    typedef typename VecOf<T>::type VT;
+    constexpr int N = VecOf<T>::N;
+    const T *x = (const T *)d.x + ck.first;
+    const T *gy = (const T *)d.gy + ck.first;
+    T *gx = WRITE_GX ? (T *)d.gx + ck.first : nullptr;
+    const int tid = threadIdx.x & (G - 1);
+    const float theta = ld_uniform(d.theta + ck.channel);
+
+    uintptr_t mis = (uintptr_t)x ^ (uintptr_t)gy;
+    if (WRITE_GX) mis |= (uintptr_t)x ^ (uintptr_t)gx;
+    const bool vector_ok = (mis & (kVecBytes - 1)) == 0;
+    const int head = vector_ok ? head_elems<T>(x, ck.n) : ck.n;
+    const int nvec = (ck.n - head) / N;
+    const VT *xv = (const VT *)(x + head);
+    const VT *gv = (const VT *)(gy + head);
+    VT *ov = WRITE_GX ? (VT *)(gx + head) : nullptr;
+
+    VT rx[kUnroll], rg[kUnroll];
+    if (nvec > 0) {
+        const int last = nvec - 1;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int v = u * G + tid;
+            v = v < last ? v : last;
+            rx[u] = ld_stream(xv + v);
+            rg[u] = ld_stream(gv + v);
+        }
+    }
+
+    const QParams p = block_params<true, G>(d, theta, bs);
+
+    double acc[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) acc[u] = 0.0;
+
+    for (int v0 = 0; v0 < nvec;) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int v = v0 + u * G + tid;
+            if (v < nvec) {
+                VT o;
+                bool any_nan = false;
+#pragma unroll
+                for (int e = 0; e < N; ++e) {
+                    bool in_range, is_nan;
+                    float t = ste_terms((float)rx[u][e], p, in_range, is_nan);
+                    o[e] = in_range ? rg[u][e] : (T)0.0f;
+                    acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t, acc[u]);
+                    any_nan |= is_nan;
+                }
+                if (any_nan) acc[u] = __builtin_nan("");   // a NaN quotient poisons its channel
+                if (WRITE_GX) st_stream(ov + v, o);
+            }
+        }
+        v0 += kUnroll * G;
+        if (v0 >= nvec) break;
+        const int last = nvec - 1;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int v = v0 + u * G + tid;
+            v = v < last ? v : last;
+            rx[u] = ld_stream(xv + v);
+            rg[u] = ld_stream(gv + v);
+        }
+    }
+
+    double sum = 0.0;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) sum += acc[u];
+    for (int i = tid; i < head; i += G) sum = backward_elem<T, WRITE_GX>(x, gy, gx, i, p, sum);
+    for (int i = head + nvec * N + tid; i < ck.n; i += G)
+        sum = backward_elem<T, WRITE_GX>(x, gy, gx, i, p, sum);
+    return sum;
+}
+
+// The same sum with the schedule for launches whose blocks are all resident at once (at most three
+// per compute unit: the 1x384x120x160 FP16 tensor).  Such a launch is one burst: every wavefront asks
 // for its whole chunk at the start, the data trickles in over the next microseconds, and whatever a
 // wavefront still has to compute after its last row has landed is added to the kernel's duration,
 // with nothing left to hide it.  So all x rows are requested before all gy rows; what depends on x
@@ -449,8 +528,8 @@ __device__ __forceinline__ double backward_elem(const T *x, const T *gy, T *gx, 
 // three wavefronts per SIMD), which costs a large launch more than the schedule gains (a
 // 15x128x120x160 FP16 tensor: 44.5 us instead of 40.7), so larger launches interleave as before.
 // The arithmetic and its order are the same in both schedules; so are the bits.
-template <typename T, bool WRITE_GX, int G, bool SHORT = false>
-__device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk &ck, BlockScale &bs)
+template <typename T, bool WRITE_GX, int G>
+__device__ __forceinline__ double backward_chunk_short(const DevTensor &d, const Chunk &ck, BlockScale &bs)
 {
     typedef typename VecOf<T>::type VT;
     constexpr int N = VecOf<T>::N;
@@ -472,25 +551,15 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
     VT rx[kUnroll], rg[kUnroll];
     auto request = [&](int v0) {      // out-of-range lanes re-read the last vector
         const int last = nvec - 1;
-        if (SHORT) {
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const int v = v0 + u * G + tid;
-                rx[u] = ld_stream(xv + (v < last ? v : last));
-            }
+        for (int u = 0; u < kUnroll; ++u) {
+            const int v = v0 + u * G + tid;
+            rx[u] = ld_stream(xv + (v < last ? v : last));
+        }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const int v = v0 + u * G + tid;
-                rg[u] = ld_stream(gv + (v < last ? v : last));
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                int v = v0 + u * G + tid;
-                v = v < last ? v : last;
-                rx[u] = ld_stream(xv + v);
-                rg[u] = ld_stream(gv + v);
-            }
+        for (int u = 0; u < kUnroll; ++u) {
+            const int v = v0 + u * G + tid;
+            rg[u] = ld_stream(gv + (v < last ? v : last));
         }
     };
     if (nvec > 0) request(0);
@@ -502,62 +571,41 @@ __device__ __forceinline__ double backward_chunk(const DevTensor &d, const Chunk
     for (int u = 0; u < kUnroll; ++u) acc[u] = 0.0;
 
     for (int v0 = 0; v0 < nvec;) {
-        if (SHORT) {
-            float t[kUnroll][N];
-            unsigned inside[kUnroll], nan_row[kUnroll];
+        float t[kUnroll][N];
+        unsigned inside[kUnroll], nan_row[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                inside[u] = 0u;
-                nan_row[u] = 0u;
+        for (int u = 0; u < kUnroll; ++u) {
+            inside[u] = 0u;
+            nan_row[u] = 0u;
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                bool in_range, is_nan;
+                t[u][e] = ste_terms((float)rx[u][e], p, in_range, is_nan);
+                inside[u] |= in_range ? 1u << e : 0u;
+                nan_row[u] |= is_nan ? 1u : 0u;
+                pin_here(t[u][e]);
+            }
+            pin_here(inside[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int v = v0 + u * G + tid;
+            if (v < nvec) {
+                VT o;
 #pragma unroll
                 for (int e = 0; e < N; ++e) {
-                    bool in_range, is_nan;
-                    t[u][e] = ste_terms((float)rx[u][e], p, in_range, is_nan);
-                    inside[u] |= in_range ? 1u << e : 0u;
-                    nan_row[u] |= is_nan ? 1u : 0u;
-                    pin_here(t[u][e]);
+                    o[e] = (inside[u] >> e & 1u) ? rg[u][e] : (T)0.0f;
+                    acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t[u][e], acc[u]);
                 }
-                pin_here(inside[u]);
+                if (nan_row[u]) acc[u] = __builtin_nan("");   // a NaN quotient poisons its channel
+                rg[u] = o;
             }
+        }
+        if (WRITE_GX) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int v = v0 + u * G + tid;
-                if (v < nvec) {
-                    VT o;
-#pragma unroll
-                    for (int e = 0; e < N; ++e) {
-                        o[e] = (inside[u] >> e & 1u) ? rg[u][e] : (T)0.0f;
-                        acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t[u][e], acc[u]);
-                    }
-                    if (nan_row[u]) acc[u] = __builtin_nan("");   // a NaN quotient poisons its channel
-                    rg[u] = o;
-                }
-            }
-            if (WRITE_GX) {
-#pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    const int v = v0 + u * G + tid;
-                    if (v < nvec) st_stream(ov + v, rg[u]);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                int v = v0 + u * G + tid;
-                if (v < nvec) {
-                    VT o;
-                    bool any_nan = false;
-#pragma unroll
-                    for (int e = 0; e < N; ++e) {
-                        bool in_range, is_nan;
-                        float t = ste_terms((float)rx[u][e], p, in_range, is_nan);
-                        o[e] = in_range ? rg[u][e] : (T)0.0f;
-                        acc[u] = __builtin_fma((double)(float)rg[u][e], (double)t, acc[u]);
-                        any_nan |= is_nan;
-                    }
-                    if (any_nan) acc[u] = __builtin_nan("");   // a NaN quotient poisons its channel
-                    if (WRITE_GX) st_stream(ov + v, o);
-                }
+                if (v < nvec) st_stream(ov + v, rg[u]);
             }
         }
         v0 += kUnroll * G;
@@ -785,7 +833,9 @@ __device__ __forceinline__ void backward_block(const DevTensor &d, const Chunk &
 
     const bool write_gx = !(d.flags & 1u);
     BlockScale bs;
-    double sum = write_gx ? backward_chunk<T, true, kBlock, SHORT>(d, ck, bs) : backward_chunk<T, false, kBlock, SHORT>(d, ck, bs);
+    double sum;
+    if (SHORT) sum = write_gx ? backward_chunk_short<T, true, kBlock>(d, ck, bs) : backward_chunk_short<T, false, kBlock>(d, ck, bs);
+    else sum = write_gx ? backward_chunk<T, true, kBlock>(d, ck, bs) : backward_chunk<T, false, kBlock>(d, ck, bs);
 
     sum = wave_sum(sum);
     if ((threadIdx.x & 63) == kSumLane) wave_part[threadIdx.x >> 6] = sum;
