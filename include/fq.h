@@ -140,8 +140,14 @@ fq_status fq_layout(const fq_tensor *t, fq_layout_info *info);
  * Zero a workspace on `stream` (a fill kernel, not a memset, so it may be captured in a
  * HIP graph).  A workspace must be zeroed once before its first use by fq_backward /
  * fq_multi_tensor in backward mode (memory that is already all zero, e.g. torch.zeros,
- * qualifies); every completed call leaves it ready for the next one.  One workspace must
- * not be used by two calls that can overlap in time.
+ * qualifies).  The kernels rely on it: a ticket or exchange slot that is not zero reads as a
+ * unit that has already arrived, and the gradients of that channel come out wrong or are never
+ * written (no kernel waits on a slot, so never a hang).  Every completed call leaves the slots
+ * zero again, so the same tensor list (same shapes and flags, any pointers) may follow without
+ * zeroing.  The partial sums and, for fq_multi_tensor and fq_plan_create, the descriptor table
+ * stay where they were written, and where the slots lie depends on the list: before a workspace
+ * serves a list of other shapes, zero it again.  One workspace must not be used by two calls
+ * that can overlap in time.
  */
 fq_status fq_workspace_init(void *workspace, size_t ws_bytes, void *hip_stream);
 
