@@ -48,6 +48,7 @@ SERIES_MIN_PER_TRAIN = 60      # ... of at least this many back-to-back launches
 TRAFFIC_BYTES_PER_LAUNCH = {
     ("feature_fp16_per_channel", "train"): 44494822,      # backward_kernel<f16>: 1.006 x the algorithmic bytes
     ("feature_fp16_per_channel", "forward"): 29588937,    # forward_kernel<f16>: 1.003 x
+    ("feature_fp16_per_channel", "codes"): 22228614,      # forward_kernel<f16, codes only>: 1.005 x
     ("train_batch_fp16", "train"): 222109624,             # 1.004 x
     ("multi_tensor_mixed", "train"): 3359417394,          # backward_multi_kernel: 1.012 x
     ("conv_weights_fp32", "train"): 17951930,             # 1.015 x
