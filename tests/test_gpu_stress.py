@@ -136,3 +136,32 @@ def test_one_scale_many_blocks_two_level_tickets():
     info = fq.fq_layout(dc.desc)
     assert info.units_per_channel > 16 and info.extra_slots in (16, 32) and info.wave_units == 0
     _repeat(case, "stress/one_scale %d blocks" % info.units_per_channel, 20)
+
+
+def test_one_workspace_serves_lists_of_other_shapes_after_zeroing():
+    """What a call leaves in a workspace (partial sums, where the slots lie) belongs to its tensor
+    list: fq_workspace_init between two lists of different shapes makes the workspace fit for the
+    next one, on the stream, with no host synchronisation in between."""
+    rng = np.random.Generator(np.random.Philox(4242))
+
+    def case(outer, channels, inner, dtype):
+        x = (rng.standard_normal((outer, channels, inner)) * 2).astype(dtype)
+        gy = rng.standard_normal(x.shape).astype(dtype)
+        theta = workloads.theta_for_scale(rng.uniform(0.02, 0.05, channels))
+        return workloads.TensorCase("reuse", x.shape, outer, channels, inner, -128, 127, x, theta, gy)
+
+    # tickets on many partial sums, then an exchange layout whose slots lie where those sums were,
+    # then two-level tickets, then the first one again
+    cases = [case(6, 48, 19200, np.float16), case(1, 384, 19200, np.float16), case(1, 1, 97 * 5120 + 13, np.float32)]
+    cases.append(cases[0])
+    dcs = [H.DeviceCase(c, want_q=False) for c in cases]
+    need = max(fq.fq_workspace_bytes(dc.desc, fq.FQ_MODE_BACKWARD) for dc in dcs)
+    ws = torch.full((need // 4,), 0x7fc00000, dtype=torch.int32, device="cuda")      # not zero: must be initialised
+    for i, dc in enumerate(dcs):
+        H.say("stress/reuse: list %d of %d on one workspace of %d bytes" % (i + 1, len(dcs), need))
+        fq.fq_workspace_init(ws)
+        fq.fq_backward(dc.desc, ws)
+    torch.cuda.synchronize()
+    for c, dc in zip(cases, dcs):
+        ref = H.oracle_forward(c)
+        H.check_backward(dc, ref[0], ref[1], "stress/reuse")
