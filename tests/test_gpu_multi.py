@@ -174,3 +174,42 @@ def test_list_mixing_block_and_wavefront_units_with_codes():
         for name in ("y", "q", "gx", "gs", "gtheta", "s"):
             a, b = getattr(one, name), getattr(d, name)
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), name
+
+
+def _random_case(rng, name, budget):
+    """One tensor of a random list: short slabs in bulk, a per-tensor scale, a feature map or an
+    arbitrary small shape, any dtype and code range, at most `budget` elements."""
+    dtype = np.float16 if rng.integers(0, 2) else np.float32
+    kind = int(rng.integers(0, 4))
+    if kind == 0:
+        inner, c, outer = int(rng.choice([9, 40, 147, 1200, 2520, 2552, 2560])), int(rng.integers(1, 200)), int(rng.integers(1, 40))
+    elif kind == 1:
+        inner, c, outer = int(rng.integers(1, 300000)), 1, int(rng.integers(1, 4))
+    elif kind == 2:
+        inner, c, outer = int(rng.choice([19200, 4800, 22560, 28800, 9600, 9601])), int(rng.integers(1, 48)), int(rng.integers(1, 6))
+    else:
+        inner, c, outer = int(rng.integers(1, 20000)), int(rng.integers(1, 16)), int(rng.integers(1, 5))
+    while outer * c * inner > budget and (outer > 1 or c > 1):
+        if outer > 1:
+            outer = (outer + 1) // 2
+        else:
+            c = (c + 1) // 2
+    inner = min(inner, budget)
+    qmin, qmax = [(-128, 127), (-127, 127), (-8, 7), (0, 15), (-2048, 2047)][int(rng.integers(0, 5))]
+    spread = float(np.exp(rng.uniform(-2, 2)))
+    x = (rng.standard_normal((outer, c, inner)) * spread).astype(dtype)
+    gy = rng.standard_normal((outer, c, inner)).astype(dtype)
+    s = spread * rng.uniform(0.5, 4.0, c) / max(abs(qmin), qmax)
+    return workloads.TensorCase(name, x.shape, outer, c, inner, qmin, qmax, x, workloads.theta_for_scale(s), gy)
+
+
+def test_randomised_lists():
+    """Sixteen seeded random lists of 2..29 tensors (every unit shape, combination protocol, dtype
+    and code range mixed in one launch; some lists have enough blocks for wavefront units)."""
+    for seed in range(16):
+        rng = np.random.default_rng(20_100 + seed)
+        n = int(rng.integers(2, 30))
+        budget = int(rng.choice([20_000, 200_000, 1_500_000]))
+        cases = [_random_case(rng, "r%d_%d" % (seed, i), budget) for i in range(n)]
+        flags = int(rng.choice([0, 0, fq.FQ_FLAG_TWO_PASS, fq.FQ_FLAG_NO_DX]))
+        _run_list(cases, "multi/random[%d] budget=%d" % (seed, budget), flags=flags, want_q=bool(rng.integers(0, 2)))
