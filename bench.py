@@ -46,13 +46,13 @@ SERIES_MIN_PER_TRAIN = 60      # ... of at least this many back-to-back launches
 # known size in the same run); the tables are in profiles/.  An entry is None until its kernel's
 # counters have been taken, and is reset to None whenever that kernel changes.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("feature_fp16_per_channel", "train"): 44494822,      # backward_kernel<f16>: 1.006 x the algorithmic bytes
-    ("feature_fp16_per_channel", "forward"): 29588937,    # forward_kernel<f16>: 1.003 x
+    ("feature_fp16_per_channel", "train"): 44488995,      # backward_kernel<f16>: 1.006 x the algorithmic bytes
+    ("feature_fp16_per_channel", "forward"): 29591391,    # forward_kernel<f16>: 1.003 x
     ("feature_fp16_per_channel", "codes"): 22228614,      # forward_kernel<f16, codes only>: 1.005 x
-    ("train_batch_fp16", "train"): 222109624,             # 1.004 x
-    ("multi_tensor_mixed", "train"): 3359417394,          # backward_multi_kernel: 1.012 x
-    ("conv_weights_fp32", "train"): 17951930,             # 1.015 x
-    ("act_fp32_per_tensor", "train"): 1981328,            # 1.075 x (a 1.8 MB launch: theta, partial sums, tickets count)
+    ("train_batch_fp16", "train"): 222084135,             # 1.004 x
+    ("multi_tensor_mixed", "train"): 3359498369,          # backward_multi_kernel: 1.012 x
+    ("conv_weights_fp32", "train"): 17958351,             # 1.015 x
+    ("act_fp32_per_tensor", "train"): 1995130,            # 1.082 x (a 1.8 MB launch: theta, partial sums, tickets count)
     ("feature_fp16_per_channel", "distill"): 44372788,    # fused kernel + the block that adds the tile sums: 1.003 x
     ("train_batch_fp16", "distill"): 221381819,           # 1.001 x
 }

@@ -150,6 +150,12 @@ struct QParams {
 
 __device__ __forceinline__ float quotient(float x, const QParams &p) { return (float)((double)x * p.rd); }
 
+// y = s * round(clip(v)) for a quotient known not to be NaN (the clip would turn NaN into lo)
+__device__ __forceinline__ float fq_value_finite(float v, const QParams &p)
+{
+    return __builtin_rintf(__builtin_amdgcn_fmed3f(v, p.lo, p.hi)) * p.s;
+}
+
 // forward value y = s * round(clip(v)); a NaN quotient gives NaN
 __device__ __forceinline__ float fq_value(float v, const QParams &p)
 {
@@ -360,9 +366,21 @@ __device__ __forceinline__ void forward_chunk(const DevTensor &d, const Chunk &c
 #pragma unroll
                 for (int e = 0; e < N; ++e) quot[e] = quotient((float)r[u][e], p);
                 if (WRITE_Y) {
+                    // A NaN quotient must come out as NaN, and the clip swallows it.  Instead of a
+                    // compare and a select per element, the row's quotients are tested in pairs
+                    // (one unordered compare sees a NaN in either operand) and only a lane that
+                    // has found one goes back over its row.
                     VT o;
+                    bool any_nan = false;
 #pragma unroll
-                    for (int e = 0; e < N; ++e) o[e] = (T)fq_value(quot[e], p);
+                    for (int e = 0; e < N; e += 2) any_nan |= __builtin_isunordered(quot[e], quot[e + 1]);
+#pragma unroll
+                    for (int e = 0; e < N; ++e) o[e] = (T)fq_value_finite(quot[e], p);
+                    if (__builtin_expect(any_nan, 0)) {
+                        asm volatile("" ::: "memory");       // keep this a branch: it is almost never taken
+#pragma unroll
+                        for (int e = 0; e < N; ++e) o[e] = (T)fq_value(quot[e], p);
+                    }
                     st_stream(yv + v, o);
                 }
                 if (EMIT_Q) {
