@@ -165,3 +165,40 @@ def test_one_workspace_serves_lists_of_other_shapes_after_zeroing():
     for c, dc in zip(cases, dcs):
         ref = H.oracle_forward(c)
         H.check_backward(dc, ref[0], ref[1], "stress/reuse")
+
+
+def test_calls_on_two_streams_with_a_workspace_each():
+    """Two streams, each with its own tensors and workspace, launching at the same time: calls
+    that do not share a workspace do not disturb each other (forward and backward, tickets on one
+    stream, exchange on the other)."""
+    a = workloads.train_batch_fp16(shape=(4, 32, 120, 160))[0]      # 8 blocks per channel: tickets
+    b = workloads.make("feature_fp16_per_channel")[0]               # 2 blocks per channel: exchange
+    want = []
+    for c in (a, b):
+        dc = H.DeviceCase(c, want_q=False)
+        fq.fq_forward(dc.desc)
+        fq.fq_backward(dc.desc, H.workspace_for(dc.desc, fq.FQ_MODE_BACKWARD))
+        torch.cuda.synchronize()
+        ref = H.oracle_forward(c)
+        H.check_forward(dc, ref, "stress/streams reference")
+        H.check_backward(dc, ref[0], ref[1], "stress/streams reference")
+        want.append([t.clone() for t in (dc.y, dc.gx, dc.gs, dc.gtheta)])
+    dcs = [H.DeviceCase(c, want_q=False) for c in (a, b)]
+    wss = [H.workspace_for(dc.desc, fq.FQ_MODE_BACKWARD) for dc in dcs]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    bad = [torch.zeros((), dtype=torch.int64, device="cuda") for _ in dcs]
+    H.say("stress/streams: 60 rounds of forward + backward on two streams at once")
+    for i in range(60):
+        for k, (dc, ws, st) in enumerate(zip(dcs, wss, streams)):
+            with torch.cuda.stream(st):
+                for t in (dc.y, dc.gx):
+                    t.view(torch.uint8).fill_(0xff)
+                dc.gs.fill_(float("nan"))
+                dc.gtheta.fill_(float("nan"))
+                fq.fq_forward(dc.desc, st.cuda_stream)
+                fq.fq_backward(dc.desc, ws, st.cuda_stream)
+                for got, w in zip((dc.y, dc.gx, dc.gs, dc.gtheta), want[k]):
+                    bad[k] += (got.view(torch.uint8) != w.view(torch.uint8)).sum()
+    torch.cuda.synchronize()
+    assert [int(x.item()) for x in bad] == [0, 0]
